@@ -1,0 +1,248 @@
+/*
+ * zi.h — C ABI of the MI355X (gfx950) optimizer hot path for offloaded,
+ * partitioned mixed-precision training.
+ *
+ * The library performs, on ONE GPU, the per-rank optimizer step over the model
+ * states a data-parallel process owns (Section 2, "ZeRO": each process updates
+ * only the optimizer states of the parameters it owns):
+ *
+ *   zi_grad_norm            global L2 norm of the low-precision gradients and
+ *                           the inf/NaN flag of dynamic loss scaling;
+ *   zi_adamw_step           fused AdamW over fp32 parameters, momentum and
+ *                           variance with low-precision gradients, writing the
+ *                           low-precision parameter copy (Section 3, "Memory
+ *                           for Model States": which arrays exist and in which
+ *                           precision; Section 2, "Adam Optimizer and Mixed
+ *                           Precision Training": updates are done in fp32);
+ *   zi_adamw_step_streamed  the same step when the fp32 states live in pinned
+ *                           host memory and move through HBM in fixed-size
+ *                           chunks, with reads, compute and writes overlapped
+ *                           through a small ring of reused staging buffers
+ *                           (Section 5.2.2: chunked step, overlap of reads,
+ *                           writes and compute; Section 6.3: reused pinned
+ *                           buffers).
+ *
+ * The step reads every state once and writes it once (Section 4.1, "AIT w.r.t.
+ * Optimizer States"): 28 bytes per element here (read p, m, v 4 B each and g
+ * 2 B; write p, m, v and the 2-byte copy).
+ *
+ * The paper cites Adam and mixed-precision training without printing their
+ * equations.  The arithmetic is the standard definition, in this fixed binary32
+ * order (round to nearest even, fused multiply-add only where fma is written):
+ *
+ *   g  = widen(g_lp) * gscale                gscale = clip / loss_scale
+ *   [ZI_MODE_ADAM_L2 only]  g = fma(weight_decay, p, g)
+ *   m' = fma(beta1, m, (1-beta1) * g)
+ *   v' = fma(beta2, v, (1-beta2) * (g * g))
+ *   d  = fma(sqrt(v'), 1/sqrt(1-beta2^step), eps)
+ *   q  = m' / d
+ *   pd = fma(-(lr*weight_decay), p, p)       [ZI_MODE_ADAMW; pd = p otherwise]
+ *   p' = fma(-(lr/(1-beta1^step)), q, pd)
+ *   p_lp = round_to_nearest_even(p')         bf16 or fp16, subnormals kept
+ *
+ * with norm = sqrt(sum g_lp^2) / loss_scale and
+ * clip = max_grad_norm / (norm + 1e-6) if that is below 1, else 1.
+ * All per-step scalars are evaluated in double and rounded once to fp32.
+ * If any gradient is +-inf or NaN the step is skipped: no byte of any state
+ * changes.
+ *
+ * General conventions
+ *   - Every pointer is a plain address.  "device" = HBM of the current HIP
+ *     device; "pinned host" = page-locked host memory (zi_pinned_alloc or any
+ *     hipHostMalloc'd block).  The caller owns every buffer it passes; the
+ *     library keeps nothing after a call returns, except inside a zi_engine.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Functions return a zi_status; negative values are errors and leave every
+ *     buffer untouched unless stated otherwise.  Nothing throws or aborts.
+ *     zi_last_error() gives the text of the calling thread's last error.
+ *   - Pointers must be aligned to their element size (4 bytes for p/m/v, 2
+ *     bytes for g and p_lp).  16-byte alignment of all arrays of a tensor, or
+ *     any common misalignment (all arrays offset by the same number of
+ *     elements from a 16-byte boundary), takes the wide path; any other
+ *     placement takes a slower element-wise path with identical results.
+ *   - numel == 0 and n_tensors == 0 are valid and do nothing.
+ *   - The library is gfx950-only and has no CPU fallback: without a usable HIP
+ *     device every compute call returns ZI_ERR_HIP.
+ */
+#ifndef ZI_H
+#define ZI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZI_OK = 0,
+    ZI_SKIPPED_OVERFLOW = 1,   /* streamed step only: gradients held inf/NaN, nothing moved */
+    ZI_ERR_INVALID_ARG = -1,
+    ZI_ERR_UNSUPPORTED = -2,
+    ZI_ERR_ALIGNMENT = -3,
+    ZI_ERR_HIP = -4,
+    ZI_ERR_NOMEM = -5
+} zi_status;
+
+typedef enum { ZI_BF16 = 0, ZI_FP16 = 1 } zi_lp_dtype;
+typedef enum { ZI_MODE_ADAMW = 0, ZI_MODE_ADAM_L2 = 1 } zi_mode;
+
+/* Hyper-parameters of one step.  Plain data, passed by pointer, read during the call only. */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int64_t step;          /* 1-based index of the step being taken; never modified */
+    float loss_scale;      /* > 0 and finite; 1 = none; raw gradients are divided by it */
+    float max_grad_norm;   /* <= 0: no clipping; needs a norm result to have any effect */
+    int32_t mode;          /* zi_mode */
+} zi_adamw_config;
+
+/* Result of zi_grad_norm.  Lives in DEVICE memory, 8-byte aligned, 24 bytes. */
+typedef struct {
+    double sumsq;          /* sum of squares of the raw (still loss-scaled) gradients */
+    double norm;           /* sqrt(sumsq) / loss_scale; meaningful only if found_inf == 0 */
+    uint32_t found_inf;    /* 1 if any gradient element is +-inf or NaN, else 0 */
+    uint32_t reserved;
+} zi_norm_result;
+
+/* One tensor of the owned partition.  All arrays hold numel elements. */
+typedef struct {
+    void* p;               /* fp32 master parameters, updated in place */
+    void* m;               /* fp32 momentum, updated in place */
+    void* v;               /* fp32 variance, updated in place */
+    const void* g;         /* low-precision gradients (device), read only */
+    void* p_lp;            /* low-precision parameter copy (device), written; may be NULL */
+    int64_t numel;
+} zi_tensor;
+
+/* Text of the calling thread's last error ("" if none).  Never NULL.  Host pointer, owned by the library. */
+const char* zi_last_error(void);
+
+/*
+ * Bytes of device scratch zi_grad_norm needs (per-block partial sums; a fixed,
+ * small size that does not grow with the inputs).  Never fails.
+ */
+size_t zi_norm_workspace_bytes(int64_t total_numel, int32_t n_tensors);
+
+/*
+ * Global gradient norm and overflow flag (the mixed-precision recipe of Section
+ * 2 implies dynamic loss scaling; the rule used is the standard one):
+ *   sumsq = sum over all tensors of g_lp^2 (accumulated in double),
+ *   norm = sqrt(sumsq) / loss_scale, found_inf = any element with an all-ones
+ *   exponent field.
+ * Only t[i].g and t[i].numel are read (device pointers; p/m/v/p_lp ignored).
+ * d_out: device, 8-byte aligned, written by the kernels on hip_stream.
+ * d_workspace: device, 16-byte aligned, >= zi_norm_workspace_bytes(); contents
+ * need no initialisation and are garbage afterwards.  Asynchronous: returns
+ * once the work is enqueued.  Two calls that share a workspace must be ordered
+ * on one stream.
+ */
+zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
+                       zi_norm_result* d_out, void* d_workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Fused AdamW step over HBM-resident state (Sections 3 and 4.1; equations in
+ * the header comment).  All arrays of every tensor are device memory; p, m, v
+ * are updated in place and p_lp (if not NULL) receives the low-precision copy.
+ * No two arrays may overlap.
+ * d_norm: device result of zi_grad_norm on the same gradients, or NULL.  With
+ * NULL there is no overflow check and no clipping: gscale = 1 / loss_scale.
+ * With a result, the kernels read it on the device: found_inf != 0 skips the
+ * whole step, otherwise the clip factor is derived from d_norm->norm.  The
+ * loss_scale given to zi_grad_norm must equal cfg->loss_scale.
+ * Asynchronous on hip_stream; the return value is ZI_OK even when the device
+ * will skip the step (read d_norm->found_inf to learn of it).
+ */
+zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, const zi_adamw_config* cfg,
+                        const zi_norm_result* d_norm, void* hip_stream);
+
+/*
+ * Streaming engine: owns n_slots staging slots in HBM (each 3 arrays of
+ * chunk_bytes_per_array for p, m, v), three HIP streams (host-to-device,
+ * compute, device-to-host; all at default priority) and the events that order
+ * slot reuse (Section 6.3: a small pool of reused buffers serves the whole
+ * state).  Created once; step calls allocate nothing.
+ * chunk_bytes_per_array: positive multiple of 256 (64 MiB is the usual value).
+ * n_slots: 2..8.  device: HIP device ordinal.
+ */
+typedef struct zi_engine zi_engine;
+
+zi_status zi_engine_create(zi_engine** out, int32_t device, size_t chunk_bytes_per_array, int32_t n_slots);
+zi_status zi_engine_destroy(zi_engine* e);   /* NULL is accepted */
+
+/*
+ * AdamW step with p, m, v in PINNED HOST memory and g, p_lp in device memory
+ * (Section 5.2.2: the state is brought to the faster memory in chunks, one chunk
+ * at a time, and written back, with reads, writes and compute overlapped).
+ * Tensors larger than a chunk are split on chunk boundaries; consecutive small
+ * tensors are packed into one slot.  Results are bit-identical to
+ * zi_adamw_step on the same values.
+ * The engine's streams first wait for the work already enqueued on hip_stream
+ * (where the gradients and d_norm were produced).  If d_norm is given, its flag
+ * is read back first; found_inf != 0 returns ZI_SKIPPED_OVERFLOW with no state
+ * moved.  BLOCKING: returns after the last device-to-host copy has completed,
+ * so the host arrays are valid on return; p_lp is complete as well.
+ * On ZI_ERR_HIP part of the host state may already have been updated.
+ */
+zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                                 const zi_adamw_config* cfg, const zi_norm_result* d_norm, void* hip_stream);
+
+/* Figures of the engine's last streamed step (host memory, filled by the call). */
+typedef struct {
+    double seconds;            /* first host-to-device issue .. last device-to-host completion */
+    uint64_t bytes_h2d;
+    uint64_t bytes_d2h;
+    int64_t n_slot_uses;       /* chunk-slots processed */
+    int64_t n_copies;          /* hipMemcpyAsync calls issued */
+    int64_t n_kernels;         /* kernel launches */
+} zi_stream_stats;
+
+zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
+
+/*
+ * Engine options.  ZI_OPT_SKIP_KERNEL = 1 runs the identical copy pipeline
+ * without launching the update (a measurement aid: the time of the pipeline
+ * with the update removed).  Default 0.
+ */
+typedef enum { ZI_OPT_SKIP_KERNEL = 0 } zi_engine_option;
+zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t value);
+
+/*
+ * Host-link probe: copies `bytes` between a pinned host buffer and the engine's
+ * staging memory `repeats` times in pieces of the engine's chunk size and
+ * reports the elapsed seconds.  mode 0 = host-to-device only, 1 = device-to-host
+ * only, 2 = both directions at once on the engine's two copy streams (then
+ * `bytes` move in EACH direction, from host_src and into host_dst).  Buffers
+ * must be pinned and hold `bytes` each; host_dst may be NULL for mode 0 and
+ * host_src for mode 1.  Blocking.
+ */
+zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, void* host_dst, size_t bytes,
+                               int32_t mode, int32_t repeats, double* seconds_out);
+
+/*
+ * Chunk plan of the streamed step, as a pure host function (no GPU needed):
+ * how a tensor list maps onto slot uses.  Segment i says that elements
+ * [elem_offset, elem_offset + count) of tensor `tensor` travel in slot use
+ * `slot_use` at element offset `slot_offset` inside the slot's arrays.
+ * Writes at most `cap` segments to `out` (may be NULL when cap == 0) and always
+ * stores the totals.  chunk_elems = chunk_bytes_per_array / 4.
+ */
+typedef struct {
+    int32_t tensor;
+    int32_t reserved;
+    int64_t elem_offset;
+    int64_t count;
+    int64_t slot_use;
+    int64_t slot_offset;
+} zi_chunk_segment;
+
+zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems, zi_chunk_segment* out,
+                         int64_t cap, int64_t* n_segments_out, int64_t* n_slot_uses_out);
+
+/* Pinned (page-locked, device-visible) host memory.  zi_pinned_free(NULL) is accepted. */
+zi_status zi_pinned_alloc(void** out, size_t bytes);
+zi_status zi_pinned_free(void* ptr);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZI_H */

@@ -1,0 +1,248 @@
+"""ctypes binding of libzi.so: argument marshalling only, same names as include/zi.h.
+
+Every step of the path runs in the HIP kernels behind the C ABI.  There is no
+CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Iterable, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libzi.so")
+
+ZI_OK = 0
+ZI_SKIPPED_OVERFLOW = 1
+ZI_ERR_INVALID_ARG = -1
+ZI_ERR_UNSUPPORTED = -2
+ZI_ERR_ALIGNMENT = -3
+ZI_ERR_HIP = -4
+ZI_ERR_NOMEM = -5
+
+ZI_BF16 = 0
+ZI_FP16 = 1
+ZI_MODE_ADAMW = 0
+ZI_MODE_ADAM_L2 = 1
+ZI_OPT_SKIP_KERNEL = 0
+
+EXPORTS = [
+    "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
+    "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
+    "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free",
+]
+
+
+class ZiError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"zi status {status}: {message}")
+        self.status = status
+        self.message = message
+
+
+class zi_adamw_config(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_int64),
+                ("loss_scale", ctypes.c_float), ("max_grad_norm", ctypes.c_float), ("mode", ctypes.c_int32)]
+
+
+class zi_norm_result(ctypes.Structure):
+    _fields_ = [("sumsq", ctypes.c_double), ("norm", ctypes.c_double), ("found_inf", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
+
+
+class zi_tensor(ctypes.Structure):
+    _fields_ = [("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("g", ctypes.c_void_p),
+                ("p_lp", ctypes.c_void_p), ("numel", ctypes.c_int64)]
+
+
+class zi_stream_stats(ctypes.Structure):
+    _fields_ = [("seconds", ctypes.c_double), ("bytes_h2d", ctypes.c_uint64), ("bytes_d2h", ctypes.c_uint64),
+                ("n_slot_uses", ctypes.c_int64), ("n_copies", ctypes.c_int64), ("n_kernels", ctypes.c_int64)]
+
+
+class zi_chunk_segment(ctypes.Structure):
+    _fields_ = [("tensor", ctypes.c_int32), ("reserved", ctypes.c_int32), ("elem_offset", ctypes.c_int64),
+                ("count", ctypes.c_int64), ("slot_use", ctypes.c_int64), ("slot_offset", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2104_07857_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.zi_last_error.restype = ctypes.c_char_p
+        L.zi_last_error.argtypes = []
+        L.zi_norm_workspace_bytes.restype = sz
+        L.zi_norm_workspace_bytes.argtypes = [i64, i32]
+        L.zi_grad_norm.restype = ctypes.c_int
+        L.zi_grad_norm.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int, ctypes.c_float, vp, vp, sz, vp]
+        L.zi_adamw_step.restype = ctypes.c_int
+        L.zi_adamw_step.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
+                                    ctypes.POINTER(zi_adamw_config), vp, vp]
+        L.zi_engine_create.restype = ctypes.c_int
+        L.zi_engine_create.argtypes = [ctypes.POINTER(vp), i32, sz, i32]
+        L.zi_engine_destroy.restype = ctypes.c_int
+        L.zi_engine_destroy.argtypes = [vp]
+        L.zi_adamw_step_streamed.restype = ctypes.c_int
+        L.zi_adamw_step_streamed.argtypes = [vp, ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
+                                             ctypes.POINTER(zi_adamw_config), vp, vp]
+        L.zi_engine_last_stats.restype = ctypes.c_int
+        L.zi_engine_last_stats.argtypes = [vp, ctypes.POINTER(zi_stream_stats)]
+        L.zi_engine_set_option.restype = ctypes.c_int
+        L.zi_engine_set_option.argtypes = [vp, i32, i64]
+        L.zi_engine_link_probe.restype = ctypes.c_int
+        L.zi_engine_link_probe.argtypes = [vp, vp, vp, sz, i32, i32, ctypes.POINTER(ctypes.c_double)]
+        L.zi_plan_chunks.restype = ctypes.c_int
+        L.zi_plan_chunks.argtypes = [ctypes.POINTER(i64), i32, i64, ctypes.POINTER(zi_chunk_segment), i64,
+                                     ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.zi_pinned_alloc.restype = ctypes.c_int
+        L.zi_pinned_alloc.argtypes = [ctypes.POINTER(vp), sz]
+        L.zi_pinned_free.restype = ctypes.c_int
+        L.zi_pinned_free.argtypes = [vp]
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        raise ZiError(status, zi_last_error())
+    return status
+
+
+def _addr(x) -> Optional[int]:
+    """Address of a torch tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    raise TypeError(f"cannot take the address of {type(x)}")
+
+
+def _numel(x) -> int:
+    if hasattr(x, "numel"):
+        return int(x.numel())
+    return int(x.size)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return None
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)     # torch.cuda.Stream
+
+
+def make_config(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, step=1, loss_scale=1.0,
+                max_grad_norm=0.0, mode=ZI_MODE_ADAMW) -> zi_adamw_config:
+    return zi_adamw_config(lr, beta1, beta2, eps, weight_decay, int(step), loss_scale, max_grad_norm, int(mode))
+
+
+def make_tensors(items: Iterable[Sequence]):
+    """ctypes array of zi_tensor from (p, m, v, g, p_lp[, numel]) tuples of tensors or addresses."""
+    items = list(items)
+    arr = (zi_tensor * max(len(items), 1))()
+    for i, it in enumerate(items):
+        p, m, v, g, p_lp = it[:5]
+        n = int(it[5]) if len(it) > 5 else _numel(g if g is not None else p)
+        arr[i] = zi_tensor(_addr(p), _addr(m), _addr(v), _addr(g), _addr(p_lp), n)
+    return arr, len(items)
+
+
+def _as_tensor_array(tensors):
+    if isinstance(tensors, tuple) and len(tensors) == 2 and isinstance(tensors[1], int) \
+            and isinstance(tensors[0], ctypes.Array):
+        return tensors
+    return make_tensors(tensors)
+
+
+# ---- the calls, named as in include/zi.h ---------------------------------------------------
+
+def zi_last_error() -> str:
+    return lib().zi_last_error().decode("utf-8", "replace")
+
+
+def zi_norm_workspace_bytes(total_numel: int = 0, n_tensors: int = 0) -> int:
+    return int(lib().zi_norm_workspace_bytes(int(total_numel), int(n_tensors)))
+
+
+def zi_grad_norm(tensors, dt: int, loss_scale: float, d_out, d_workspace, workspace_bytes: Optional[int] = None,
+                 stream=None) -> int:
+    arr, n = _as_tensor_array(tensors)
+    if workspace_bytes is None:
+        workspace_bytes = d_workspace.numel() * d_workspace.element_size()
+    return _check(lib().zi_grad_norm(arr, n, int(dt), float(loss_scale), _addr(d_out), _addr(d_workspace),
+                                     int(workspace_bytes), _stream(stream)))
+
+
+def zi_adamw_step(tensors, dt: int, cfg: zi_adamw_config, d_norm=None, stream=None) -> int:
+    arr, n = _as_tensor_array(tensors)
+    return _check(lib().zi_adamw_step(arr, n, int(dt), ctypes.byref(cfg) if cfg is not None else None,
+                                      _addr(d_norm), _stream(stream)))
+
+
+def zi_engine_create(device: int, chunk_bytes_per_array: int, n_slots: int) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().zi_engine_create(ctypes.byref(h), int(device), int(chunk_bytes_per_array), int(n_slots)))
+    return h.value
+
+
+def zi_engine_destroy(engine) -> int:
+    return _check(lib().zi_engine_destroy(engine))
+
+
+def zi_adamw_step_streamed(engine, tensors, dt: int, cfg: zi_adamw_config, d_norm=None, stream=None) -> int:
+    arr, n = _as_tensor_array(tensors)
+    return _check(lib().zi_adamw_step_streamed(engine, arr, n, int(dt),
+                                               ctypes.byref(cfg) if cfg is not None else None,
+                                               _addr(d_norm), _stream(stream)))
+
+
+def zi_engine_last_stats(engine) -> zi_stream_stats:
+    st = zi_stream_stats()
+    _check(lib().zi_engine_last_stats(engine, ctypes.byref(st)))
+    return st
+
+
+def zi_engine_set_option(engine, option: int, value: int) -> int:
+    return _check(lib().zi_engine_set_option(engine, int(option), int(value)))
+
+
+def zi_engine_link_probe(engine, host_src, host_dst, nbytes: int, mode: int, repeats: int = 1) -> float:
+    sec = ctypes.c_double()
+    _check(lib().zi_engine_link_probe(engine, _addr(host_src), _addr(host_dst), int(nbytes), int(mode),
+                                      int(repeats), ctypes.byref(sec)))
+    return sec.value
+
+
+def zi_plan_chunks(numel: Sequence[int], chunk_elems: int):
+    """(segments, n_slot_uses); segments are zi_chunk_segment records."""
+    n = len(numel)
+    arr = (ctypes.c_int64 * max(n, 1))(*[int(x) for x in numel])
+    nseg, nuse = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().zi_plan_chunks(arr, n, int(chunk_elems), None, 0, ctypes.byref(nseg), ctypes.byref(nuse)))
+    out = (zi_chunk_segment * max(nseg.value, 1))()
+    _check(lib().zi_plan_chunks(arr, n, int(chunk_elems), out, nseg.value, ctypes.byref(nseg), ctypes.byref(nuse)))
+    return [out[i] for i in range(nseg.value)], nuse.value
+
+
+def zi_pinned_alloc(nbytes: int) -> int:
+    h = ctypes.c_void_p()
+    _check(lib().zi_pinned_alloc(ctypes.byref(h), int(nbytes)))
+    return h.value
+
+
+def zi_pinned_free(ptr) -> int:
+    return _check(lib().zi_pinned_free(ptr))

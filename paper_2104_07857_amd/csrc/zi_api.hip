@@ -1,0 +1,685 @@
+// C-ABI entry points: argument validation, per-step scalars, launch planning, and the
+// pinned-host <-> HBM streaming engine.  See include/zi.h for the contract of every call.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "zi_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+zi_status fail(zi_status st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+#define ZI_HIP(call)                                                                                  \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess)                                                                         \
+            return fail(ZI_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+zi_status check_dtype(int dt)
+{
+    if (dt != ZI_BF16 && dt != ZI_FP16) return fail(ZI_ERR_INVALID_ARG, "unknown low-precision dtype %d", dt);
+    return ZI_OK;
+}
+
+zi_status check_config(const zi_adamw_config* c)
+{
+    if (!c) return fail(ZI_ERR_INVALID_ARG, "cfg is NULL");
+    if (c->step < 1) return fail(ZI_ERR_INVALID_ARG, "step must be >= 1 (got %lld)", (long long)c->step);
+    if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f)) return fail(ZI_ERR_INVALID_ARG, "beta1 must be in [0,1)");
+    if (!(c->beta2 >= 0.0f && c->beta2 < 1.0f)) return fail(ZI_ERR_INVALID_ARG, "beta2 must be in [0,1)");
+    if (!(c->eps >= 0.0f) || std::isinf(c->eps)) return fail(ZI_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!std::isfinite(c->lr)) return fail(ZI_ERR_INVALID_ARG, "lr must be finite");
+    if (!std::isfinite(c->weight_decay)) return fail(ZI_ERR_INVALID_ARG, "weight_decay must be finite");
+    if (!(c->loss_scale > 0.0f) || std::isinf(c->loss_scale))
+        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    if (std::isnan(c->max_grad_norm)) return fail(ZI_ERR_INVALID_ARG, "max_grad_norm is NaN");
+    if (c->mode != ZI_MODE_ADAMW && c->mode != ZI_MODE_ADAM_L2)
+        return fail(ZI_ERR_INVALID_ARG, "unknown mode %d", c->mode);
+    return ZI_OK;
+}
+
+// Tensor list of a step: pointers present and aligned to their element size.
+zi_status check_step_tensors(const zi_tensor* t, int32_t n)
+{
+    if (n < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    for (int32_t i = 0; i < n; ++i) {
+        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+        if (t[i].numel == 0) continue;
+        if (!t[i].p || !t[i].m || !t[i].v || !t[i].g)
+            return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v and g must not be NULL", i);
+        if (!aligned(t[i].p, 4) || !aligned(t[i].m, 4) || !aligned(t[i].v, 4))
+            return fail(ZI_ERR_ALIGNMENT, "tensor %d: p, m, v must be 4-byte aligned", i);
+        if (!aligned(t[i].g, 2) || !aligned(t[i].p_lp, 2))
+            return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
+        if (t[i].p == t[i].m || t[i].p == t[i].v || t[i].m == t[i].v || t[i].g == t[i].p_lp)
+            return fail(ZI_ERR_INVALID_ARG, "tensor %d: arrays must not alias each other", i);
+    }
+    return ZI_OK;
+}
+
+// Per-step constants, in double, each rounded once to fp32.
+zi::StepConsts make_consts(const zi_adamw_config& c)
+{
+    zi::StepConsts k{};
+    const double b1 = (double)c.beta1, b2 = (double)c.beta2;
+    const double bc1 = 1.0 - std::pow(b1, (double)c.step);
+    const double bc2 = 1.0 - std::pow(b2, (double)c.step);
+    k.beta1 = c.beta1;
+    k.beta2 = c.beta2;
+    k.omb1 = (float)(1.0 - b1);
+    k.omb2 = (float)(1.0 - b2);
+    k.eps = c.eps;
+    k.step_size = (float)((double)c.lr / bc1);
+    k.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    k.decay = c.mode == ZI_MODE_ADAMW ? (float)((double)c.lr * (double)c.weight_decay) : 0.0f;
+    k.weight_decay = c.weight_decay;
+    k.loss_scale = c.loss_scale;
+    k.max_grad_norm = c.max_grad_norm;
+    k.host_gscale = (float)(1.0 / (double)c.loss_scale);
+    return k;
+}
+
+// Number of leading elements before every array of the tensor is 16-byte aligned, or -1 if the
+// arrays have no common such index (then only the element-wise kernel applies).
+int common_head(const void* p, const void* m, const void* v, const void* g, const void* p_lp)
+{
+    const int h = (int)((8 - (reinterpret_cast<uintptr_t>(g) / 2) % 8) % 8);
+    if (p_lp && (int)((8 - (reinterpret_cast<uintptr_t>(p_lp) / 2) % 8) % 8) != h) return -1;
+    const void* f[3] = {p, m, v};
+    for (const void* x : f)
+        if ((int)((4 - (reinterpret_cast<uintptr_t>(x) / 4) % 4) % 4) != h % 4) return -1;
+    return h;
+}
+
+// Issues the fused step over a list of device-resident segments.
+struct StepIssuer {
+    zi::StepArgs args{};
+    uint32_t tiles = 0;
+    int dt;
+    bool l2;
+    hipStream_t stream;
+    int64_t launches = 0;
+
+    StepIssuer(const zi::StepConsts& c, const zi_norm_result* d_norm, int dt_, bool l2_, hipStream_t s)
+        : dt(dt_), l2(l2_), stream(s)
+    {
+        args.c = c;
+        args.d_norm = d_norm;
+        args.n_desc = 0;
+    }
+
+    hipError_t flush()
+    {
+        hipError_t e = hipSuccess;
+        if (args.n_desc > 0) {
+            e = zi::launch_step_wide(args, tiles, dt, l2, stream);
+            ++launches;
+        }
+        args.n_desc = 0;
+        tiles = 0;
+        return e;
+    }
+
+    hipError_t add(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, int64_t numel)
+    {
+        if (numel <= 0) return hipSuccess;
+        zi::StepDesc d{};
+        d.p = p; d.m = m; d.v = v; d.g = g; d.p_lp = p_lp; d.numel = numel;
+        const int h = common_head(p, m, v, g, p_lp);
+        if (h < 0) {
+            d.head = 0;
+            d.first_tile = 0;
+            ++launches;
+            return zi::launch_step_elementwise(d, args.c, args.d_norm, dt, l2, stream);
+        }
+        d.head = (int32_t)(h < numel ? h : numel);
+        const int64_t nvec = (numel - d.head) / zi::kVec;
+        int64_t nt = (nvec + zi::kStepTileVecs - 1) / zi::kStepTileVecs;
+        if (nt < 1) nt = 1;                       // the first tile also owns the unaligned ends
+        if (nt > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (args.n_desc == zi::kMaxStepDesc || (uint64_t)tiles + (uint64_t)nt > 0x7FFFFFFFull) {
+            hipError_t e = flush();
+            if (e != hipSuccess) return e;
+        }
+        d.first_tile = tiles;
+        args.t[args.n_desc++] = d;
+        tiles += (uint32_t)nt;
+        return hipSuccess;
+    }
+};
+
+}  // namespace
+
+// ============================================================================ plain queries
+
+extern "C" const char* zi_last_error(void) { return g_err; }
+
+extern "C" size_t zi_norm_workspace_bytes(int64_t, int32_t)
+{
+    return (size_t)zi::kMaxPartials * sizeof(zi::NormPartial);
+}
+
+// ================================================================================ grad norm
+
+extern "C" zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
+                                  zi_norm_result* d_out, void* d_workspace, size_t workspace_bytes,
+                                  void* hip_stream)
+{
+    if (zi_status st = check_dtype((int)dt)) return st;
+    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
+        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    if (!d_out) return fail(ZI_ERR_INVALID_ARG, "d_out is NULL");
+    if (!aligned(d_out, 8)) return fail(ZI_ERR_ALIGNMENT, "d_out must be 8-byte aligned");
+    if (!d_workspace) return fail(ZI_ERR_INVALID_ARG, "d_workspace is NULL");
+    if (!aligned(d_workspace, 16)) return fail(ZI_ERR_ALIGNMENT, "d_workspace must be 16-byte aligned");
+    if (workspace_bytes < zi_norm_workspace_bytes(0, 0))
+        return fail(ZI_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes,
+                    zi_norm_workspace_bytes(0, 0));
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+        if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
+        if (!aligned(t[i].g, 2)) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
+    }
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    zi::NormPartial* partials = (zi::NormPartial*)d_workspace;
+
+    // A workgroup covers at least four tile iterations of its tensor; at most kBlocksPerTensor
+    // workgroups walk one tensor, so the partial count stays small whatever the size.
+    constexpr int64_t kMinElemsPerBlock = 4 * zi::kNormTileElems;
+    constexpr int64_t kBlocksPerTensor = 4096;
+
+    zi::NormArgs a{};
+    a.partials = partials;
+    a.partial_base = 0;
+    a.n_desc = 0;
+    uint32_t blocks = 0;       // blocks of the launch being assembled
+    uint32_t used = 0;         // partials written since the last finalize
+    int finalized = 0;
+
+    auto flush_launch = [&]() -> hipError_t {
+        hipError_t e = hipSuccess;
+        if (a.n_desc > 0) e = zi::launch_norm_partials(a, blocks, (int)dt, s);
+        used += blocks;
+        a.partial_base = used;
+        a.n_desc = 0;
+        blocks = 0;
+        return e;
+    };
+    auto flush_partials = [&]() -> hipError_t {
+        hipError_t e = zi::launch_norm_finalize(partials, used, loss_scale, finalized, d_out, s);
+        finalized = 1;
+        used = 0;
+        a.partial_base = 0;
+        return e;
+    };
+
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const int64_t n = t[i].numel;
+        if (n == 0) continue;
+        int64_t nb = (n + kMinElemsPerBlock - 1) / kMinElemsPerBlock;
+        if (nb > kBlocksPerTensor) nb = kBlocksPerTensor;
+        if (a.n_desc == zi::kMaxNormDesc) ZI_HIP(flush_launch());
+        if ((uint64_t)used + blocks + (uint64_t)nb > zi::kMaxPartials) {
+            ZI_HIP(flush_launch());
+            ZI_HIP(flush_partials());
+        }
+        zi::NormDesc d{};
+        d.g = (const uint16_t*)t[i].g;
+        d.numel = n;
+        const int h = (int)((8 - (reinterpret_cast<uintptr_t>(t[i].g) / 2) % 8) % 8);
+        d.head = (int32_t)(h < n ? h : n);
+        d.first_block = blocks;
+        d.n_blocks = (uint32_t)nb;
+        a.t[a.n_desc++] = d;
+        blocks += (uint32_t)nb;
+    }
+    ZI_HIP(flush_launch());
+    ZI_HIP(flush_partials());   // also writes zeros for an empty list
+    return ZI_OK;
+}
+
+// =============================================================================== resident step
+
+extern "C" zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                                   const zi_adamw_config* cfg, const zi_norm_result* d_norm, void* hip_stream)
+{
+    if (zi_status st = check_dtype((int)dt)) return st;
+    if (zi_status st = check_config(cfg)) return st;
+    if (zi_status st = check_step_tensors(t, n_tensors)) return st;
+    if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
+
+    const zi::StepConsts k = make_consts(*cfg);
+    StepIssuer issue(k, d_norm, (int)dt, cfg->mode == ZI_MODE_ADAM_L2, (hipStream_t)hip_stream);
+    for (int32_t i = 0; i < n_tensors; ++i)
+        ZI_HIP(issue.add((float*)t[i].p, (float*)t[i].m, (float*)t[i].v, (const uint16_t*)t[i].g,
+                         (uint16_t*)t[i].p_lp, t[i].numel));
+    ZI_HIP(issue.flush());
+    return ZI_OK;
+}
+
+// ================================================================================== chunk plan
+
+namespace {
+
+constexpr int64_t kPackAlign = 64;   // packed segments start on 256-byte boundaries of the slot arrays
+constexpr int64_t kPhasePad = 8;     // room for up to 7 lead-in elements that keep 16-byte phases equal
+
+struct Segment {
+    int32_t tensor;
+    int64_t elem_offset, count, slot_use, slot_offset;
+};
+
+// Pass 1: every whole chunk of every tensor takes a slot use of its own, in list order.
+// Pass 2: what is left (tensors shorter than a chunk and the remainders of long ones) is packed
+// first-fit, in list order, into shared slot uses of at most kMaxStepDesc segments each, so a
+// list with many tiny tensors between giant ones costs one extra slot use, not one per tensor.
+void plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems, std::vector<Segment>& out,
+                 int64_t& n_uses)
+{
+    out.clear();
+    int64_t use = 0;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const int64_t whole = numel[i] / chunk_elems;
+        for (int64_t c = 0; c < whole; ++c) out.push_back({i, c * chunk_elems, chunk_elems, use++, 0});
+    }
+    int64_t fill = 0;          // next free element of the open packed slot use
+    int packed = 0;            // segments in the open packed slot use
+    bool open = false;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const int64_t off = numel[i] / chunk_elems * chunk_elems;
+        const int64_t left = numel[i] - off;
+        if (left == 0) continue;
+        if (open && (fill + left + kPhasePad > chunk_elems || packed == zi::kMaxStepDesc)) {
+            ++use;
+            open = false;
+        }
+        if (!open) { open = true; fill = 0; packed = 0; }
+        out.push_back({i, off, left, use, fill});
+        ++packed;
+        fill = (fill + left + kPhasePad + kPackAlign - 1) / kPackAlign * kPackAlign;
+    }
+    if (open) ++use;
+    n_uses = use;
+}
+
+}  // namespace
+
+extern "C" zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems,
+                                    zi_chunk_segment* out, int64_t cap, int64_t* n_segments_out,
+                                    int64_t* n_slot_uses_out)
+{
+    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n_tensors > 0 && !numel) return fail(ZI_ERR_INVALID_ARG, "numel is NULL");
+    if (chunk_elems < kPackAlign || chunk_elems % kPackAlign)
+        return fail(ZI_ERR_INVALID_ARG, "chunk_elems must be a positive multiple of %lld", (long long)kPackAlign);
+    if (cap < 0 || (cap > 0 && !out)) return fail(ZI_ERR_INVALID_ARG, "bad output buffer");
+    if (!n_segments_out || !n_slot_uses_out) return fail(ZI_ERR_INVALID_ARG, "output counters are NULL");
+    for (int32_t i = 0; i < n_tensors; ++i)
+        if (numel[i] < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+    std::vector<Segment> segs;
+    int64_t uses = 0;
+    try {
+        plan_chunks(numel, n_tensors, chunk_elems, segs, uses);
+    } catch (const std::bad_alloc&) {
+        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+    }
+    for (int64_t i = 0; i < (int64_t)segs.size() && i < cap; ++i) {
+        out[i].tensor = segs[i].tensor;
+        out[i].reserved = 0;
+        out[i].elem_offset = segs[i].elem_offset;
+        out[i].count = segs[i].count;
+        out[i].slot_use = segs[i].slot_use;
+        out[i].slot_offset = segs[i].slot_offset;
+    }
+    *n_segments_out = (int64_t)segs.size();
+    *n_slot_uses_out = uses;
+    return ZI_OK;
+}
+
+// ============================================================================ streaming engine
+
+struct zi_engine {
+    int device = 0;
+    size_t chunk_bytes = 0;
+    int64_t chunk_elems = 0;
+    int n_slots = 0;
+    size_t array_bytes = 0;            // chunk_bytes + room for phase lead-in
+    char* staging = nullptr;           // n_slots * 3 * array_bytes
+    hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
+    hipEvent_t ev_h2d[8] = {}, ev_k[8] = {}, ev_d2h[8] = {};
+    hipEvent_t ev_in = nullptr, ev_out = nullptr;
+    zi_norm_result* h_norm = nullptr;  // pinned landing place of the norm result
+    int64_t skip_kernel = 0;
+    zi_stream_stats stats{};
+    uint32_t magic = 0;
+
+    float* slot_array(int slot, int which) const
+    {
+        return reinterpret_cast<float*>(staging + ((size_t)slot * 3 + which) * array_bytes);
+    }
+};
+
+namespace {
+
+constexpr uint32_t kEngineMagic = 0x5A49454Eu;
+
+zi_status check_engine(const zi_engine* e)
+{
+    if (!e) return fail(ZI_ERR_INVALID_ARG, "engine is NULL");
+    if (e->magic != kEngineMagic) return fail(ZI_ERR_INVALID_ARG, "engine is not valid (destroyed?)");
+    return ZI_OK;
+}
+
+void engine_release(zi_engine* e)
+{
+    for (int i = 0; i < 8; ++i) {
+        if (e->ev_h2d[i]) (void)hipEventDestroy(e->ev_h2d[i]);
+        if (e->ev_k[i]) (void)hipEventDestroy(e->ev_k[i]);
+        if (e->ev_d2h[i]) (void)hipEventDestroy(e->ev_d2h[i]);
+    }
+    if (e->ev_in) (void)hipEventDestroy(e->ev_in);
+    if (e->ev_out) (void)hipEventDestroy(e->ev_out);
+    if (e->s_h2d) (void)hipStreamDestroy(e->s_h2d);
+    if (e->s_k) (void)hipStreamDestroy(e->s_k);
+    if (e->s_d2h) (void)hipStreamDestroy(e->s_d2h);
+    if (e->staging) (void)hipFree(e->staging);
+    if (e->h_norm) (void)hipHostFree(e->h_norm);
+    e->magic = 0;
+    delete e;
+}
+
+}  // namespace
+
+extern "C" zi_status zi_engine_create(zi_engine** out, int32_t device, size_t chunk_bytes_per_array,
+                                      int32_t n_slots)
+{
+    if (!out) return fail(ZI_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (device < 0) return fail(ZI_ERR_INVALID_ARG, "device < 0");
+    if (chunk_bytes_per_array == 0 || chunk_bytes_per_array % 256)
+        return fail(ZI_ERR_INVALID_ARG, "chunk_bytes_per_array must be a positive multiple of 256");
+    if (chunk_bytes_per_array > ((size_t)1 << 34))
+        return fail(ZI_ERR_INVALID_ARG, "chunk_bytes_per_array above 16 GiB");
+    if (n_slots < 2 || n_slots > 8) return fail(ZI_ERR_INVALID_ARG, "n_slots must be in 2..8");
+
+    int count = 0;
+    ZI_HIP(hipGetDeviceCount(&count));
+    if (device >= count) return fail(ZI_ERR_INVALID_ARG, "device %d does not exist (%d devices)", device, count);
+    ZI_HIP(hipSetDevice(device));
+
+    zi_engine* e = new (std::nothrow) zi_engine();
+    if (!e) return fail(ZI_ERR_NOMEM, "out of host memory");
+    e->device = device;
+    e->chunk_bytes = chunk_bytes_per_array;
+    e->chunk_elems = (int64_t)(chunk_bytes_per_array / 4);
+    e->n_slots = n_slots;
+    e->array_bytes = chunk_bytes_per_array + 256;
+
+#define ZI_HIP_E(call)                                                                           \
+    do {                                                                                         \
+        hipError_t e_ = (call);                                                                  \
+        if (e_ != hipSuccess) {                                                                  \
+            engine_release(e);                                                                   \
+            return fail(e_ == hipErrorOutOfMemory ? ZI_ERR_NOMEM : ZI_ERR_HIP, "%s failed: %s",   \
+                        #call, hipGetErrorString(e_));                                           \
+        }                                                                                        \
+    } while (0)
+
+    ZI_HIP_E(hipMalloc((void**)&e->staging, (size_t)n_slots * 3 * e->array_bytes));
+    ZI_HIP_E(hipHostMalloc((void**)&e->h_norm, sizeof(zi_norm_result), hipHostMallocDefault));
+    ZI_HIP_E(hipStreamCreateWithFlags(&e->s_h2d, hipStreamNonBlocking));
+    ZI_HIP_E(hipStreamCreateWithFlags(&e->s_k, hipStreamNonBlocking));
+    ZI_HIP_E(hipStreamCreateWithFlags(&e->s_d2h, hipStreamNonBlocking));
+    for (int i = 0; i < n_slots; ++i) {
+        ZI_HIP_E(hipEventCreateWithFlags(&e->ev_h2d[i], hipEventDisableTiming));
+        ZI_HIP_E(hipEventCreateWithFlags(&e->ev_k[i], hipEventDisableTiming));
+        ZI_HIP_E(hipEventCreateWithFlags(&e->ev_d2h[i], hipEventDisableTiming));
+    }
+    ZI_HIP_E(hipEventCreateWithFlags(&e->ev_in, hipEventDisableTiming));
+    ZI_HIP_E(hipEventCreateWithFlags(&e->ev_out, hipEventDisableTiming));
+#undef ZI_HIP_E
+    e->magic = kEngineMagic;
+    *out = e;
+    return ZI_OK;
+}
+
+extern "C" zi_status zi_engine_destroy(zi_engine* e)
+{
+    if (!e) return ZI_OK;
+    if (zi_status st = check_engine(e)) return st;
+    (void)hipSetDevice(e->device);
+    (void)hipStreamSynchronize(e->s_h2d);
+    (void)hipStreamSynchronize(e->s_k);
+    (void)hipStreamSynchronize(e->s_d2h);
+    engine_release(e);
+    return ZI_OK;
+}
+
+extern "C" zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (!out) return fail(ZI_ERR_INVALID_ARG, "out is NULL");
+    *out = e->stats;
+    return ZI_OK;
+}
+
+extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t value)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (option == ZI_OPT_SKIP_KERNEL) {
+        e->skip_kernel = value != 0;
+        return ZI_OK;
+    }
+    return fail(ZI_ERR_INVALID_ARG, "unknown engine option %d", option);
+}
+
+extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                                            const zi_adamw_config* cfg, const zi_norm_result* d_norm,
+                                            void* hip_stream)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (zi_status st = check_dtype((int)dt)) return st;
+    if (zi_status st = check_config(cfg)) return st;
+    if (zi_status st = check_step_tensors(t, n_tensors)) return st;
+    if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
+
+    ZI_HIP(hipSetDevice(e->device));
+    hipStream_t user = (hipStream_t)hip_stream;
+    e->stats = zi_stream_stats{};
+
+    // The state must be page-locked: a pageable source would turn every copy into a staged,
+    // synchronous one and the pipeline would silently serialise.
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (t[i].numel == 0) continue;
+        const void* arrs[3] = {t[i].p, t[i].m, t[i].v};
+        for (const void* a : arrs) {
+            hipPointerAttribute_t attr{};
+            hipError_t pe = hipPointerGetAttributes(&attr, a);
+            if (pe != hipSuccess || attr.type != hipMemoryTypeHost) {
+                (void)hipGetLastError();
+                return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be pinned host memory", i);
+            }
+        }
+    }
+
+    std::vector<int64_t> numel((size_t)n_tensors);
+    for (int32_t i = 0; i < n_tensors; ++i) numel[(size_t)i] = t[i].numel;
+    std::vector<Segment> segs;
+    int64_t n_uses = 0;
+    try {
+        plan_chunks(numel.data(), n_tensors, e->chunk_elems, segs, n_uses);
+    } catch (const std::bad_alloc&) {
+        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+    }
+
+    // Overflow flag first: a skipped step moves nothing (4 bytes decide about gigabytes of traffic).
+    if (d_norm) {
+        ZI_HIP(hipMemcpyAsync(e->h_norm, d_norm, sizeof(zi_norm_result), hipMemcpyDeviceToHost, user));
+        ZI_HIP(hipStreamSynchronize(user));
+        if (e->h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
+    }
+
+    // Everything already enqueued on the caller's stream (gradients, norm) happens before our work.
+    ZI_HIP(hipEventRecord(e->ev_in, user));
+    ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
+    ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
+
+    const zi::StepConsts k = make_consts(*cfg);
+    const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
+    const auto t0 = std::chrono::steady_clock::now();
+
+    size_t si = 0;
+    for (int64_t use = 0; use < n_uses; ++use) {
+        const int slot = (int)(use % e->n_slots);
+        // Slot reuse is ordered by the event of the device-to-host copies that last emptied it.
+        // Waiting for the OLDEST slot use keeps the host n_slots uses ahead of the copy engines.
+        if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_d2h[slot]));
+
+        const size_t s_begin = si;
+        while (si < segs.size() && segs[si].slot_use == use) ++si;
+
+        struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes; };
+        Placed placed[zi::kMaxStepDesc];
+        StepIssuer issue(k, d_norm, (int)dt, l2, e->s_k);
+        int np = 0;
+        for (size_t j = s_begin; j < si; ++j, ++np) {
+            const Segment& sg = segs[j];
+            const zi_tensor& T = t[sg.tensor];
+            const uint16_t* g = (const uint16_t*)T.g + sg.elem_offset;
+            // Lead-in elements that give the staged fp32 arrays the 16-byte phase of the gradients.
+            const int64_t phase = (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 8);
+            const int64_t so = sg.slot_offset + phase;
+            Placed& P = placed[np];
+            P.dp = e->slot_array(slot, 0) + so;
+            P.dm = e->slot_array(slot, 1) + so;
+            P.dv = e->slot_array(slot, 2) + so;
+            P.hp = (char*)T.p + sg.elem_offset * 4;
+            P.hm = (char*)T.m + sg.elem_offset * 4;
+            P.hv = (char*)T.v + sg.elem_offset * 4;
+            P.bytes = (size_t)sg.count * 4;
+            ZI_HIP(hipMemcpyAsync(P.dp, P.hp, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+            ZI_HIP(hipMemcpyAsync(P.dm, P.hm, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+            ZI_HIP(hipMemcpyAsync(P.dv, P.hv, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+            e->stats.bytes_h2d += 3 * P.bytes;
+            e->stats.n_copies += 3;
+        }
+        ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
+
+        ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
+        if (!e->skip_kernel) {
+            np = 0;
+            for (size_t j = s_begin; j < si; ++j, ++np) {
+                const Segment& sg = segs[j];
+                const zi_tensor& T = t[sg.tensor];
+                ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv,
+                                 (const uint16_t*)T.g + sg.elem_offset,
+                                 T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr, sg.count));
+            }
+            ZI_HIP(issue.flush());
+            e->stats.n_kernels += issue.launches;
+        }
+        ZI_HIP(hipEventRecord(e->ev_k[slot], e->s_k));
+
+        ZI_HIP(hipStreamWaitEvent(e->s_d2h, e->ev_k[slot], 0));
+        for (int q = 0; q < np; ++q) {
+            const Placed& P = placed[q];
+            ZI_HIP(hipMemcpyAsync(P.hp, P.dp, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+            ZI_HIP(hipMemcpyAsync(P.hm, P.dm, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+            ZI_HIP(hipMemcpyAsync(P.hv, P.dv, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+            e->stats.bytes_d2h += 3 * P.bytes;
+            e->stats.n_copies += 3;
+        }
+        ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
+        ++e->stats.n_slot_uses;
+    }
+
+    // Host arrays are valid on return; later work on the caller's stream sees the finished p_lp.
+    ZI_HIP(hipStreamSynchronize(e->s_d2h));
+    ZI_HIP(hipEventRecord(e->ev_out, e->s_k));
+    ZI_HIP(hipStreamWaitEvent(user, e->ev_out, 0));
+    ZI_HIP(hipStreamSynchronize(e->s_k));
+    e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return ZI_OK;
+}
+
+extern "C" zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, void* host_dst, size_t bytes,
+                                          int32_t mode, int32_t repeats, double* seconds_out)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (mode < 0 || mode > 2) return fail(ZI_ERR_INVALID_ARG, "mode must be 0, 1 or 2");
+    if (repeats < 1) return fail(ZI_ERR_INVALID_ARG, "repeats < 1");
+    if (!seconds_out) return fail(ZI_ERR_INVALID_ARG, "seconds_out is NULL");
+    if ((mode == 0 || mode == 2) && !host_src) return fail(ZI_ERR_INVALID_ARG, "host_src is NULL");
+    if ((mode == 1 || mode == 2) && !host_dst) return fail(ZI_ERR_INVALID_ARG, "host_dst is NULL");
+    if (bytes == 0) return fail(ZI_ERR_INVALID_ARG, "bytes is 0");
+    ZI_HIP(hipSetDevice(e->device));
+    ZI_HIP(hipStreamSynchronize(e->s_h2d));
+    ZI_HIP(hipStreamSynchronize(e->s_d2h));
+
+    // Host-to-device pieces land in the p arrays of the slots, device-to-host pieces leave from
+    // the m arrays, so the two directions never touch the same staging bytes.
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int r = 0; r < repeats; ++r) {
+        int piece = 0;
+        for (size_t off = 0; off < bytes; off += e->chunk_bytes, ++piece) {
+            const size_t nb = bytes - off < e->chunk_bytes ? bytes - off : e->chunk_bytes;
+            const int slot = piece % e->n_slots;
+            if (mode == 0 || mode == 2)
+                ZI_HIP(hipMemcpyAsync(e->slot_array(slot, 0), (const char*)host_src + off, nb,
+                                      hipMemcpyHostToDevice, e->s_h2d));
+            if (mode == 1 || mode == 2)
+                ZI_HIP(hipMemcpyAsync((char*)host_dst + off, e->slot_array(slot, 1), nb, hipMemcpyDeviceToHost,
+                                      e->s_d2h));
+        }
+    }
+    ZI_HIP(hipStreamSynchronize(e->s_h2d));
+    ZI_HIP(hipStreamSynchronize(e->s_d2h));
+    *seconds_out = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return ZI_OK;
+}
+
+// ================================================================================ pinned memory
+
+extern "C" zi_status zi_pinned_alloc(void** out, size_t bytes)
+{
+    if (!out) return fail(ZI_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (bytes == 0) return fail(ZI_ERR_INVALID_ARG, "bytes is 0");
+    hipError_t e = hipHostMalloc(out, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        *out = nullptr;
+        return fail(e == hipErrorOutOfMemory ? ZI_ERR_NOMEM : ZI_ERR_HIP, "hipHostMalloc(%zu) failed: %s", bytes,
+                    hipGetErrorString(e));
+    }
+    return ZI_OK;
+}
+
+extern "C" zi_status zi_pinned_free(void* ptr)
+{
+    if (!ptr) return ZI_OK;
+    ZI_HIP(hipHostFree(ptr));
+    return ZI_OK;
+}

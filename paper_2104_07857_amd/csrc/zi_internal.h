@@ -1,0 +1,83 @@
+// Internal interface between the C-ABI layer (host) and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "zi.h"
+
+namespace zi {
+
+constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes per workgroup
+constexpr int kVec = 8;              // elements per 16-byte vector of a 2-byte array
+constexpr int kStepUnroll = 2;       // 16-byte vectors of the gradient array per thread per tile
+constexpr int kStepTileVecs = kThreads * kStepUnroll;
+constexpr int64_t kStepTileElems = (int64_t)kStepTileVecs * kVec;   // 4096 elements per tile
+constexpr int kMaxStepDesc = 32;     // tensors (or segments) per fused-step launch
+
+constexpr int kNormUnroll = 4;
+constexpr int kNormTileVecs = kThreads * kNormUnroll;
+constexpr int64_t kNormTileElems = (int64_t)kNormTileVecs * kVec;   // 8192 elements per block iteration
+constexpr int kMaxNormDesc = 64;     // gradient tensors per partial-sum launch
+constexpr uint32_t kMaxPartials = 16384;   // per-block partial results the workspace holds
+
+// One per-block partial of the gradient reduction (device workspace element).
+struct NormPartial {
+    double sumsq;
+    uint32_t found_inf;
+    uint32_t pad;
+};
+
+// Per-step constants of the update, every one already rounded to fp32 on the host.
+struct StepConsts {
+    float beta1, beta2, omb1, omb2, eps, step_size, inv_sqrt_bc2, decay, weight_decay;
+    float loss_scale;      // as given by the caller
+    float max_grad_norm;   // <= 0: no clipping
+    float host_gscale;     // 1 / loss_scale, used when no norm result is given
+};
+
+// One tensor (or one segment of one) as the fused step sees it.  All pointers are device memory.
+// `head` elements come before the first index at which every array is 16-byte aligned.
+struct StepDesc {
+    float* p;
+    float* m;
+    float* v;
+    const uint16_t* g;
+    uint16_t* p_lp;        // may be null
+    int64_t numel;
+    int32_t head;          // 0..7
+    uint32_t first_tile;   // index of this tensor's first tile within the launch
+};
+
+struct StepArgs {
+    StepDesc t[kMaxStepDesc];
+    int32_t n_desc;
+    StepConsts c;
+    const zi_norm_result* d_norm;   // device, may be null
+};
+
+struct NormDesc {
+    const uint16_t* g;
+    int64_t numel;
+    int32_t head;          // 0..7 elements before the first 16-byte aligned one
+    uint32_t first_block;
+    uint32_t n_blocks;
+    uint32_t pad;
+};
+
+struct NormArgs {
+    NormDesc t[kMaxNormDesc];
+    int32_t n_desc;
+    uint32_t partial_base;          // index of this launch's first partial
+    NormPartial* partials;
+};
+
+// Launchers (zi_kernels.hip).  Each returns the hipError_t of the launch.
+hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2, hipStream_t s);
+hipError_t launch_step_elementwise(const StepDesc& d, const StepConsts& c, const zi_norm_result* d_norm, int dt,
+                                   bool l2, hipStream_t s);
+hipError_t launch_norm_partials(const NormArgs& a, uint32_t n_blocks, int dt, hipStream_t s);
+hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, float loss_scale, int accumulate,
+                                zi_norm_result* d_out, hipStream_t s);
+
+}  // namespace zi

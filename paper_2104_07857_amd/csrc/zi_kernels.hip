@@ -1,0 +1,450 @@
+// gfx950 kernels of the optimizer hot path: gradient sum of squares + overflow flag,
+// and the fused AdamW read-modify-write pass.
+//
+// Both are pure HBM streams (Section 4.1, "AIT w.r.t. Optimizer States": the step reads every
+// state once and writes it once), so the design is about bytes, not flops: every array is
+// accessed with 16-byte loads and stores, a thread has all loads of a tile in flight before
+// the first use, nothing goes through LDS except the block reduction of the norm, and no
+// matrix core is involved because there is no contraction.
+//
+// Arithmetic order of the update: see include/zi.h.  Compile with -ffp-contract=off so that the
+// only fused multiply-adds are the ones written as fma below.
+#include <hip/hip_runtime.h>
+
+#include "zi_internal.h"
+
+namespace zi {
+
+// ---------------------------------------------------------------------------------- casts
+
+template <int DT>
+__device__ __forceinline__ float widen16(uint32_t h);
+
+template <>
+__device__ __forceinline__ float widen16<ZI_BF16>(uint32_t h)
+{
+    return __uint_as_float(h << 16);
+}
+
+template <>
+__device__ __forceinline__ float widen16<ZI_FP16>(uint32_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);   // exact, fp16 subnormals included
+}
+
+// low and high half of a packed pair
+template <int DT>
+__device__ __forceinline__ void widen_pair(uint32_t w, float& lo, float& hi)
+{
+    if constexpr (DT == ZI_BF16) {
+        lo = __uint_as_float(w << 16);
+        hi = __uint_as_float(w & 0xFFFF0000u);
+    } else {
+        lo = widen16<ZI_FP16>(w & 0xFFFFu);
+        hi = widen16<ZI_FP16>(w >> 16);
+    }
+}
+
+// fp32 -> low precision, round to nearest even (the hardware converters of gfx950 in the default
+// rounding mode; fp16 subnormals are produced, NaN stays NaN, overflow gives inf).
+template <int DT>
+__device__ __forceinline__ uint32_t narrow16(float x)
+{
+    if constexpr (DT == ZI_BF16) {
+        return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)x);
+    } else {
+        return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)x);
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
+{
+    return narrow16<DT>(lo) | (narrow16<DT>(hi) << 16);
+}
+
+// ------------------------------------------------------------------------- the update itself
+
+template <bool L2>
+__device__ __forceinline__ void adamw_element(float& p, float& m, float& v, float g, float gscale,
+                                              const StepConsts& c)
+{
+    g = g * gscale;
+    if constexpr (L2) g = __builtin_fmaf(c.weight_decay, p, g);
+    const float m1 = __builtin_fmaf(c.beta1, m, c.omb1 * g);
+    const float v1 = __builtin_fmaf(c.beta2, v, c.omb2 * (g * g));
+    const float d = __builtin_fmaf(__builtin_sqrtf(v1), c.inv_sqrt_bc2, c.eps);
+    const float q = m1 / d;
+    const float pd = __builtin_fmaf(-c.decay, p, p);
+    p = __builtin_fmaf(-c.step_size, q, pd);
+    m = m1;
+    v = v1;
+}
+
+// Skip decision and gradient factor, from the device-resident norm result.
+// Returns false if the step must be skipped.
+__device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, const StepConsts& c, float& gscale)
+{
+    gscale = c.host_gscale;
+    if (d_norm) {
+        if (d_norm->found_inf) return false;
+        const double norm = d_norm->norm;
+        const double mx = (double)c.max_grad_norm;
+        double clip = 1.0;
+        if (c.max_grad_norm > 0.0f && norm + 1e-6 > mx) clip = mx / (norm + 1e-6);
+        gscale = (float)(clip / (double)c.loss_scale);
+    }
+    return true;
+}
+
+template <int DT, bool L2>
+__device__ __forceinline__ void step_scalar_at(const StepDesc& T, int64_t i, float gscale, const StepConsts& c)
+{
+    float p = T.p[i], m = T.m[i], v = T.v[i];
+    const float g = widen16<DT>(T.g[i]);
+    adamw_element<L2>(p, m, v, g, gscale, c);
+    T.p[i] = p;
+    T.m[i] = m;
+    T.v[i] = v;
+    if (T.p_lp) T.p_lp[i] = (uint16_t)narrow16<DT>(p);
+}
+
+struct Vec8 {
+    float4 a, b;
+};
+
+template <int DT, bool L2>
+__device__ __forceinline__ uint4 step_vec8(Vec8& p, Vec8& m, Vec8& v, const uint4 g, float gscale,
+                                           const StepConsts& c)
+{
+    float g0, g1, g2, g3, g4, g5, g6, g7;
+    widen_pair<DT>(g.x, g0, g1);
+    widen_pair<DT>(g.y, g2, g3);
+    widen_pair<DT>(g.z, g4, g5);
+    widen_pair<DT>(g.w, g6, g7);
+    adamw_element<L2>(p.a.x, m.a.x, v.a.x, g0, gscale, c);
+    adamw_element<L2>(p.a.y, m.a.y, v.a.y, g1, gscale, c);
+    adamw_element<L2>(p.a.z, m.a.z, v.a.z, g2, gscale, c);
+    adamw_element<L2>(p.a.w, m.a.w, v.a.w, g3, gscale, c);
+    adamw_element<L2>(p.b.x, m.b.x, v.b.x, g4, gscale, c);
+    adamw_element<L2>(p.b.y, m.b.y, v.b.y, g5, gscale, c);
+    adamw_element<L2>(p.b.z, m.b.z, v.b.z, g6, gscale, c);
+    adamw_element<L2>(p.b.w, m.b.w, v.b.w, g7, gscale, c);
+    uint4 lp;
+    lp.x = narrow_pair<DT>(p.a.x, p.a.y);
+    lp.y = narrow_pair<DT>(p.a.z, p.a.w);
+    lp.z = narrow_pair<DT>(p.b.x, p.b.y);
+    lp.w = narrow_pair<DT>(p.b.z, p.b.w);
+    return lp;
+}
+
+// One workgroup = one tile of kStepTileElems elements of one tensor.  blockIdx.x counts tiles over
+// all tensors of the launch; first_tile locates the tensor.
+template <int DT, bool L2>
+__global__ __launch_bounds__(kThreads) void adamw_wide_kernel(const StepArgs a)
+{
+    float gscale;
+    if (!step_prologue(a.d_norm, a.c, gscale)) return;
+
+    uint32_t tile = blockIdx.x;
+    int d = 0;
+    while (d + 1 < a.n_desc && tile >= a.t[d + 1].first_tile) ++d;
+    const StepDesc& T = a.t[d];
+    tile -= T.first_tile;
+
+    const int64_t head = T.head;
+    const int64_t nvec = (T.numel - head) / kVec;          // whole 8-element vectors of the body
+    const int64_t body_end = head + nvec * kVec;
+
+    // Elements before and after the aligned body (at most 7 each), by the tensor's first tile.
+    if (tile == 0) {
+        const int64_t t = threadIdx.x;
+        if (t < head) step_scalar_at<DT, L2>(T, t, gscale, a.c);
+        const int64_t tail = T.numel - body_end;
+        if (t >= 8 && t - 8 < tail) step_scalar_at<DT, L2>(T, body_end + (t - 8), gscale, a.c);
+    }
+
+    float4* __restrict__ p4 = reinterpret_cast<float4*>(T.p + head);
+    float4* __restrict__ m4 = reinterpret_cast<float4*>(T.m + head);
+    float4* __restrict__ v4 = reinterpret_cast<float4*>(T.v + head);
+    const uint4* __restrict__ g4 = reinterpret_cast<const uint4*>(T.g + head);
+    uint4* __restrict__ lp4 = T.p_lp ? reinterpret_cast<uint4*>(T.p_lp + head) : nullptr;
+
+    const int64_t vec0 = (int64_t)tile * kStepTileVecs + threadIdx.x;
+
+    if ((int64_t)(tile + 1) * kStepTileVecs <= nvec) {
+        // full tile: every load is issued before the first result is needed
+        Vec8 p[kStepUnroll], m[kStepUnroll], v[kStepUnroll];
+        uint4 g[kStepUnroll];
+#pragma unroll
+        for (int u = 0; u < kStepUnroll; ++u) {
+            const int64_t iv = vec0 + (int64_t)u * kThreads;
+            g[u] = g4[iv];
+            p[u].a = p4[2 * iv];
+            p[u].b = p4[2 * iv + 1];
+            m[u].a = m4[2 * iv];
+            m[u].b = m4[2 * iv + 1];
+            v[u].a = v4[2 * iv];
+            v[u].b = v4[2 * iv + 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kStepUnroll; ++u) {
+            const int64_t iv = vec0 + (int64_t)u * kThreads;
+            const uint4 lp = step_vec8<DT, L2>(p[u], m[u], v[u], g[u], gscale, a.c);
+            p4[2 * iv] = p[u].a;
+            p4[2 * iv + 1] = p[u].b;
+            m4[2 * iv] = m[u].a;
+            m4[2 * iv + 1] = m[u].b;
+            v4[2 * iv] = v[u].a;
+            v4[2 * iv + 1] = v[u].b;
+            if (lp4) lp4[iv] = lp;
+        }
+    } else {
+        for (int u = 0; u < kStepUnroll; ++u) {
+            const int64_t iv = vec0 + (int64_t)u * kThreads;
+            if (iv < nvec) {
+                Vec8 p, m, v;
+                const uint4 g = g4[iv];
+                p.a = p4[2 * iv];
+                p.b = p4[2 * iv + 1];
+                m.a = m4[2 * iv];
+                m.b = m4[2 * iv + 1];
+                v.a = v4[2 * iv];
+                v.b = v4[2 * iv + 1];
+                const uint4 lp = step_vec8<DT, L2>(p, m, v, g, gscale, a.c);
+                p4[2 * iv] = p.a;
+                p4[2 * iv + 1] = p.b;
+                m4[2 * iv] = m.a;
+                m4[2 * iv + 1] = m.b;
+                v4[2 * iv] = v.a;
+                v4[2 * iv + 1] = v.b;
+                if (lp4) lp4[iv] = lp;
+            }
+        }
+    }
+}
+
+// Any placement of the arrays: one element per thread per iteration, grid-stride.
+template <int DT, bool L2>
+__global__ __launch_bounds__(kThreads) void adamw_elementwise_kernel(const StepDesc T, const StepConsts c,
+                                                                     const zi_norm_result* d_norm)
+{
+    float gscale;
+    if (!step_prologue(d_norm, c, gscale)) return;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < T.numel; i += stride)
+        step_scalar_at<DT, L2>(T, i, gscale, c);
+}
+
+hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2, hipStream_t s)
+{
+    if (n_tiles == 0) return hipSuccess;
+    const dim3 grid(n_tiles), block(kThreads);
+    if (dt == ZI_BF16) {
+        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, true>), grid, block, 0, s, a);
+        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, false>), grid, block, 0, s, a);
+    } else {
+        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, true>), grid, block, 0, s, a);
+        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, false>), grid, block, 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_step_elementwise(const StepDesc& d, const StepConsts& c, const zi_norm_result* d_norm, int dt,
+                                   bool l2, hipStream_t s)
+{
+    if (d.numel <= 0) return hipSuccess;
+    int64_t blocks = (d.numel + kThreads - 1) / kThreads;
+    if (blocks > 65536) blocks = 65536;
+    const dim3 grid((uint32_t)blocks), block(kThreads);
+    if (dt == ZI_BF16) {
+        if (l2) hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_BF16, true>), grid, block, 0, s, d, c, d_norm);
+        else    hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_BF16, false>), grid, block, 0, s, d, c, d_norm);
+    } else {
+        if (l2) hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_FP16, true>), grid, block, 0, s, d, c, d_norm);
+        else    hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_FP16, false>), grid, block, 0, s, d, c, d_norm);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------- gradient sum of squares + overflow flag
+
+// Bit 15 / bit 31 of the result is set iff the exponent field of the low / high half is all ones.
+template <int DT>
+__device__ __forceinline__ uint32_t nonfinite_bits(uint32_t w)
+{
+    constexpr uint32_t mask = DT == ZI_BF16 ? 0x7F807F80u : 0x7C007C00u;
+    constexpr uint32_t one = DT == ZI_BF16 ? 0x00800080u : 0x04000400u;
+    return ((w & mask) + one) & 0x80008000u;
+}
+
+template <int DT>
+__device__ __forceinline__ void sumsq_word(uint32_t w, double& acc0, double& acc1, uint32_t& flag)
+{
+    flag |= nonfinite_bits<DT>(w);
+    float lo, hi;
+    widen_pair<DT>(w, lo, hi);
+    const double dlo = (double)lo, dhi = (double)hi;
+    acc0 = __builtin_fma(dlo, dlo, acc0);
+    acc1 = __builtin_fma(dhi, dhi, acc1);
+}
+
+template <int DT>
+__device__ __forceinline__ void sumsq_vec(const uint4 g, double& acc0, double& acc1, uint32_t& flag)
+{
+    sumsq_word<DT>(g.x, acc0, acc1, flag);
+    sumsq_word<DT>(g.y, acc0, acc1, flag);
+    sumsq_word<DT>(g.z, acc0, acc1, flag);
+    sumsq_word<DT>(g.w, acc0, acc1, flag);
+}
+
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t wave_or(uint32_t x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x |= __shfl_xor(x, off, 64);
+    return x;
+}
+
+// Two-level reduction: wavefront shuffles, then one LDS slot per wavefront.  Result valid in thread 0.
+template <int NWAVES>
+__device__ __forceinline__ void block_reduce(double& sum, uint32_t& flag)
+{
+    __shared__ double s_sum[NWAVES];
+    __shared__ uint32_t s_flag[NWAVES];
+    sum = wave_sum(sum);
+    flag = wave_or(flag);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        s_sum[wave] = sum;
+        s_flag[wave] = flag;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        uint32_t f = 0;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) {
+            t += s_sum[w];
+            f |= s_flag[w];
+        }
+        sum = t;
+        flag = f;
+    }
+}
+
+// Each workgroup walks its tensor with a stride of n_blocks tiles and leaves one partial.
+// Squares are accumulated in double: exact products, and a finite gradient whose square would
+// overflow fp32 still gives a finite sum.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void sumsq_partial_kernel(const NormArgs a)
+{
+    uint32_t b = blockIdx.x;
+    int d = 0;
+    while (d + 1 < a.n_desc && b >= a.t[d + 1].first_block) ++d;
+    const NormDesc& T = a.t[d];
+    b -= T.first_block;
+
+    const int64_t head = T.head;
+    const int64_t nvec = (T.numel - head) / kVec;
+    const int64_t body_end = head + nvec * kVec;
+    const uint4* __restrict__ g4 = reinterpret_cast<const uint4*>(T.g + head);
+
+    double acc0 = 0.0, acc1 = 0.0;
+    uint32_t flag = 0;
+
+    if (b == 0) {
+        const int64_t t = threadIdx.x;
+        const int64_t tail = T.numel - body_end;
+        int64_t idx = -1;
+        if (t < head) idx = t;
+        else if (t >= 8 && t - 8 < tail) idx = body_end + (t - 8);
+        if (idx >= 0) {
+            const uint32_t h = T.g[idx];
+            flag |= nonfinite_bits<DT>(h);
+            const double x = (double)widen16<DT>(h);
+            acc0 = __builtin_fma(x, x, acc0);
+        }
+    }
+
+    const int64_t stride = (int64_t)T.n_blocks * kNormTileVecs;
+    for (int64_t base = (int64_t)b * kNormTileVecs; base < nvec; base += stride) {
+        const int64_t iv = base + threadIdx.x;
+        if (base + kNormTileVecs <= nvec) {
+            uint4 g[kNormUnroll];
+#pragma unroll
+            for (int u = 0; u < kNormUnroll; ++u) g[u] = g4[iv + (int64_t)u * kThreads];
+#pragma unroll
+            for (int u = 0; u < kNormUnroll; ++u) sumsq_vec<DT>(g[u], acc0, acc1, flag);
+        } else {
+            for (int u = 0; u < kNormUnroll; ++u) {
+                const int64_t j = iv + (int64_t)u * kThreads;
+                if (j < nvec) sumsq_vec<DT>(g4[j], acc0, acc1, flag);
+            }
+        }
+    }
+
+    double sum = acc0 + acc1;
+    block_reduce<kThreads / 64>(sum, flag);
+    if (threadIdx.x == 0) {
+        NormPartial out;
+        out.sumsq = sum;
+        out.found_inf = flag ? 1u : 0u;
+        out.pad = 0;
+        a.partials[a.partial_base + blockIdx.x] = out;
+    }
+}
+
+constexpr int kFinalThreads = 1024;
+
+// One workgroup adds the partials in a fixed order (so the result does not depend on scheduling)
+// and writes the device-resident result.
+__global__ __launch_bounds__(kFinalThreads) void norm_finalize_kernel(const NormPartial* __restrict__ partials,
+                                                                      uint32_t count, float loss_scale,
+                                                                      int accumulate, zi_norm_result* out)
+{
+    double sum = 0.0;
+    uint32_t flag = 0;
+    for (uint32_t i = threadIdx.x; i < count; i += kFinalThreads) {
+        sum += partials[i].sumsq;
+        flag |= partials[i].found_inf;
+    }
+    block_reduce<kFinalThreads / 64>(sum, flag);
+    if (threadIdx.x == 0) {
+        if (accumulate) {
+            sum += out->sumsq;
+            flag |= out->found_inf;
+        }
+        zi_norm_result r;
+        r.sumsq = sum;
+        r.norm = __builtin_sqrt(sum) / (double)loss_scale;
+        r.found_inf = flag ? 1u : 0u;
+        r.reserved = 0;
+        *out = r;
+    }
+}
+
+hipError_t launch_norm_partials(const NormArgs& a, uint32_t n_blocks, int dt, hipStream_t s)
+{
+    if (n_blocks == 0) return hipSuccess;
+    const dim3 grid(n_blocks), block(kThreads);
+    if (dt == ZI_BF16) hipLaunchKernelGGL((sumsq_partial_kernel<ZI_BF16>), grid, block, 0, s, a);
+    else               hipLaunchKernelGGL((sumsq_partial_kernel<ZI_FP16>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, float loss_scale, int accumulate,
+                                zi_norm_result* d_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(norm_finalize_kernel, dim3(1), dim3(kFinalThreads), 0, s, partials, count, loss_scale,
+                       accumulate, d_out);
+    return hipGetLastError();
+}
+
+}  // namespace zi

@@ -1,0 +1,105 @@
+"""Parity of zi_grad_norm (sum of squares, norm, overflow flag) with the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2104_07857_amd as zi
+import zi_synth
+from gpu_util import NormBuffers, TOL_NORM_REL, progress, to_dev
+
+pytestmark = pytest.mark.gpu
+
+NORM_TILE = 8192
+
+
+def _gpu_norm(gs, dt, loss_scale=1.0, nb=None):
+    nb = nb or NormBuffers()
+    devs = [g if isinstance(g, torch.Tensor) else to_dev(g) for g in gs]
+    zi.zi_grad_norm([(None, None, None, d, None, d.numel()) for d in devs], dt, loss_scale, nb.out, nb.ws)
+    torch.cuda.synchronize()
+    return nb.read()
+
+
+def _grads(n, dt, seed, std=1e-3):
+    g = np.empty(n, np.uint16)
+    zi_synth.fill_normal_lp(g, n, seed, zi_synth.STREAM_G, dt, std=std)
+    return g
+
+
+@pytest.mark.parametrize("dt", [zi.ZI_BF16, zi.ZI_FP16])
+@pytest.mark.parametrize("n", [0, 1, 7, 8, 9, NORM_TILE - 1, NORM_TILE, NORM_TILE + 1, 4 * NORM_TILE + 3,
+                               1_000_003, (1 << 24) + 5])
+def test_single_tensor_sizes(n, dt):
+    g = _grads(n, dt, 100 + n, std=1e-3 if dt == zi.ZI_BF16 else 65.536)
+    want, wflag = oracle.grad_sumsq([g], dt)
+    sumsq, norm, flag = _gpu_norm([g], dt, loss_scale=4.0)
+    assert flag == wflag == 0
+    assert abs(sumsq - want) <= 1e-12 * max(want, 1e-300)      # double accumulation on both sides
+    assert abs(norm - math.sqrt(want) / 4.0) <= TOL_NORM_REL * max(math.sqrt(want) / 4.0, 1e-300)
+
+
+def test_unaligned_views_and_lists():
+    dt = zi.ZI_BF16
+    base = to_dev(_grads(200_000, dt, 5))
+    host = base.cpu().numpy().view(np.uint16)
+    cuts = [(0, 0), (1, 1), (3, 50_001), (50_001, 50_001 + 7), (60_000, 199_999), (199_999, 200_000)]
+    views = [base[a:b] for a, b in cuts]
+    want, _ = oracle.grad_sumsq([host[a:b].copy() for a, b in cuts], dt)
+    sumsq, norm, flag = _gpu_norm(views, dt)
+    assert flag == 0 and abs(sumsq - want) <= 1e-12 * want
+    # many tensors: more than one launch's table holds, and more partials than one finalize pass takes
+    many = [base[i * 37:(i * 37) + 29] for i in range(300)]
+    want, _ = oracle.grad_sumsq([host[i * 37:(i * 37) + 29].copy() for i in range(300)], dt)
+    sumsq, _, _ = _gpu_norm(many, dt)
+    assert abs(sumsq - want) <= 1e-12 * want
+    # empty list: a defined zero result
+    assert _gpu_norm([], dt) == (0.0, 0.0, 0)
+
+
+def test_partial_budget_overflow_path():
+    """A list whose block count exceeds the workspace's partial capacity forces intermediate finalizes."""
+    dt = zi.ZI_BF16
+    n = 4096 * 4 * NORM_TILE         # one tensor that takes the per-tensor maximum of 4096 blocks
+    big = to_dev(_grads(n, dt, 6))
+    host = big.cpu().numpy().view(np.uint16)
+    one, _ = oracle.grad_sumsq([host], dt)
+    sumsq, _, flag = _gpu_norm([big] * 5, dt)          # 5 x 4096 blocks > 16384 partials
+    assert flag == 0 and abs(sumsq - 5 * one) <= 1e-12 * 5 * one
+
+
+@pytest.mark.parametrize("dt,specials,finite_max", [
+    (zi.ZI_BF16, [0x7F80, 0xFF80, 0x7FC0, 0x7F81, 0xFFFF], [0x7F7F, 0xFF7F]),
+    (zi.ZI_FP16, [0x7C00, 0xFC00, 0x7E00, 0x7C01, 0xFFFF], [0x7BFF, 0xFBFF])])
+def test_flag_is_bit_exact(dt, specials, finite_max):
+    n = 3 * NORM_TILE + 5
+    base = _grads(n, dt, 9)
+    nb = NormBuffers()
+    for s in specials:
+        for pos in (0, 1, 7, 8, n - 1, n - 6, NORM_TILE, 2 * NORM_TILE + 17):
+            g = base.copy()
+            g[pos] = s
+            assert _gpu_norm([g], dt, nb=nb)[2] == 1 == oracle.grad_sumsq([g], dt)[1], (hex(s), pos)
+    # unaligned view with the special value in the scalar head and tail
+    for pos in (0, 2, n - 4):
+        g = base.copy()
+        g[pos + 3] = specials[0]
+        d = to_dev(g)
+        assert _gpu_norm([d[3:]], dt, nb=nb)[2] == 1
+    # the largest finite values are not an overflow; their squares stay finite in the double sum
+    for s in finite_max:
+        g = base.copy()
+        g[11] = s
+        want, wflag = oracle.grad_sumsq([g], dt)
+        sumsq, _, flag = _gpu_norm([g], dt, nb=nb)
+        assert flag == wflag == 0 and math.isfinite(sumsq) and abs(sumsq - want) <= 1e-12 * want
+    assert _gpu_norm([base], dt, nb=nb)[2] == 0      # and the flag resets between calls
+
+
+def test_constant_closed_form():
+    g = torch.full((1 << 22,), 0x3E80, dtype=torch.int16, device="cuda:0")     # bf16 0.25
+    sumsq, norm, flag = _gpu_norm([g], zi.ZI_BF16, loss_scale=2.0)
+    assert sumsq == 0.0625 * (1 << 22) and norm == 0.25 * 2048 / 2.0 and flag == 0
+    progress("norm closed form ok")

@@ -1,0 +1,166 @@
+"""The streamed step (state in pinned host memory, chunked through HBM) against the oracle and the resident step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2104_07857_amd as zi
+import zi_synth
+from gpu_util import NormBuffers, compare_state, gen_numpy, oracle_cfg, progress, to_dev, to_np, zi_cfg
+
+pytestmark = pytest.mark.gpu
+
+
+def _pinned(a: np.ndarray) -> torch.Tensor:
+    t = torch.empty(a.size, dtype=torch.float32, pin_memory=True)
+    t.numpy()[:] = a
+    return t
+
+
+def _stream_list(engine, host, dt, ocfg, zcfg, use_norm, g_offset=0):
+    """host: list of (p, m, v, g) numpy.  Returns expected (oracle) and got (streamed) lists + info."""
+    exp = [(p.copy(), m.copy(), v.copy(), g, np.zeros(p.size, np.uint16)) for (p, m, v, g) in host]
+    info = oracle.step(exp, dt, ocfg, use_norm)
+    pinned = [tuple(_pinned(a) for a in t[:3]) for t in host]
+    dg, dlp = [], []
+    for t in host:
+        n = t[3].size
+        gbuf = torch.zeros(n + 8, dtype=torch.int16, device="cuda:0")
+        lbuf = torch.zeros(n + 8, dtype=torch.int16, device="cuda:0")
+        gbuf[g_offset:g_offset + n].copy_(to_dev(t[3]))
+        dg.append(gbuf[g_offset:g_offset + n])
+        dlp.append(lbuf[g_offset:g_offset + n])
+    nb = None
+    if use_norm:
+        nb = NormBuffers()
+        zi.zi_grad_norm([(None, None, None, g, None, g.numel()) for g in dg], dt, ocfg.loss_scale, nb.out, nb.ws)
+    tl = [(pp, pm, pv, g, lp, g.numel()) for (pp, pm, pv), g, lp in zip(pinned, dg, dlp)]
+    st = zi.zi_adamw_step_streamed(engine, tl, dt, zcfg, None if nb is None else nb.out,
+                                   torch.cuda.current_stream())
+    got = [(pp.numpy().copy(), pm.numpy().copy(), pv.numpy().copy(), to_np(lp))
+           for (pp, pm, pv), lp in zip(pinned, dlp)]
+    return exp, got, dict(status=st, oracle=info, norm=nb.read() if nb else None)
+
+
+@pytest.fixture(scope="module")
+def engine():
+    e = zi.zi_engine_create(0, 64 * 1024, 3)          # 16384-element chunks: many slot uses at small sizes
+    yield e
+    zi.zi_engine_destroy(e)
+
+
+@pytest.mark.parametrize("n", [1, 100, 16384 - 8, 16384, 16384 + 1, 5 * 16384 + 777, 40 * 16384])
+def test_flat_state_with_tail_chunk(engine, n):
+    w = zi_synth.workload("c2")
+    host = [gen_numpy(zi_synth.StateSpec(2000 + n, zi.ZI_BF16), n)]
+    exp, got, info = _stream_list(engine, host, zi.ZI_BF16, oracle_cfg(w), zi_cfg(w), use_norm=False)
+    assert info["status"] == zi.ZI_OK
+    rep = compare_state((exp[0][0], exp[0][1], exp[0][2], exp[0][4]), got[0], zi.ZI_BF16, f"n={n} ")
+    st = zi.zi_engine_last_stats(engine)
+    assert st.bytes_h2d == st.bytes_d2h == 12 * n
+    assert st.n_slot_uses == (n + 16383) // 16384
+    if n == 5 * 16384 + 777:
+        progress("streamed flat: " + rep)
+
+
+def test_streamed_equals_resident_bit_for_bit(engine):
+    """Chunking must not change a single bit (the update is independent per element)."""
+    n = 7 * 16384 + 4321
+    w = zi_synth.workload("c2")
+    host = [gen_numpy(zi_synth.StateSpec(77, zi.ZI_BF16), n)]
+    _, got, _ = _stream_list(engine, host, zi.ZI_BF16, oracle_cfg(w), zi_cfg(w), use_norm=False)
+    p, m, v, g = (to_dev(a) for a in host[0])
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    zi.zi_adamw_step([(p, m, v, g, lp, n)], zi.ZI_BF16, zi_cfg(w))
+    torch.cuda.synchronize()
+    for a, b in zip(got[0], (to_np(p), to_np(m), to_np(v), to_np(lp))):
+        assert np.array_equal(a.view(np.uint32) if a.dtype == np.float32 else a,
+                              b.view(np.uint32) if b.dtype == np.float32 else b)
+
+
+@pytest.mark.parametrize("g_offset", [0, 3])
+def test_ragged_list_with_packing_and_global_clip(engine, g_offset):
+    """Workload 4 in miniature: 4 layers x 12 tensors (hidden 128: weights span several chunks, biases
+    and LayerNorm vectors are packed into shared slots), separate pinned arrays, one global clip."""
+    h = 128
+    w = zi_synth.workload("c4")
+    numel = [n for _ in range(4) for (_, n) in zi_synth.transformer_layer_shapes(h)]
+    spec = zi_synth.StateSpec(w["spec"].seed, zi.ZI_BF16, g_std=2e-3)
+    host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(numel)]
+    exp, got, info = _stream_list(engine, host, zi.ZI_BF16, oracle_cfg(w), zi_cfg(w), use_norm=True,
+                                  g_offset=g_offset)
+    assert info["status"] == zi.ZI_OK and info["oracle"]["found_inf"] == 0
+    assert abs(info["norm"][1] - info["oracle"]["norm"]) <= 1e-6 * info["oracle"]["norm"]
+    assert oracle.scalars(oracle_cfg(w), info["oracle"]["sumsq"]).clip < 1.0
+    for i, (e, g) in enumerate(zip(exp, got)):
+        rep = compare_state((e[0], e[1], e[2], e[4]), g, zi.ZI_BF16, f"tensor {i} ")
+    segs, uses = zi.zi_plan_chunks(numel, 16384)
+    st = zi.zi_engine_last_stats(engine)
+    assert st.n_slot_uses == uses and st.bytes_h2d == 12 * sum(numel) == st.bytes_d2h
+    progress(f"streamed ragged (g offset {g_offset}): {uses} slot uses, {st.n_kernels} launches; last {rep}")
+
+
+def test_overflow_skips_without_moving_state(engine):
+    w = zi_synth.workload("c3")
+    n = 3 * 16384 + 5
+    p, m, v, g = gen_numpy(w["spec"], n)
+    g[zi_synth.pick_index(1, 2, n)] = 0xFC00          # -inf
+    exp, got, info = _stream_list(engine, [(p, m, v, g)], zi.ZI_FP16, oracle_cfg(w), zi_cfg(w), use_norm=True)
+    assert info["status"] == zi.ZI_SKIPPED_OVERFLOW and info["oracle"]["skipped"]
+    for a, b in zip((p, m, v), got[0][:3]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert not got[0][3].any()
+    st = zi.zi_engine_last_stats(engine)
+    assert st.bytes_h2d == 0 and st.bytes_d2h == 0 and st.n_kernels == 0
+
+
+def test_step_allocates_nothing_and_rejects_pageable_state(engine):
+    n = 4 * 16384
+    w = zi_synth.workload("c2")
+    host = gen_numpy(w["spec"], n)
+    pp, pm, pv = (_pinned(a) for a in host[:3])
+    g = to_dev(host[3])
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(3):
+        zi.zi_adamw_step_streamed(engine, [(pp, pm, pv, g, lp, n)], zi.ZI_BF16, zi_cfg(w))
+    free1, _ = torch.cuda.mem_get_info()
+    assert free1 == free0, "the engine's step must not allocate device memory"
+    pageable = np.zeros(n, np.float32)
+    with pytest.raises(zi.ZiError) as e:
+        zi.zi_adamw_step_streamed(engine, [(pageable, pm, pv, g, lp, n)], zi.ZI_BF16, zi_cfg(w))
+    assert e.value.status == zi.ZI_ERR_INVALID_ARG and "pinned" in e.value.message
+
+
+def test_copy_only_option_and_link_probe(engine):
+    n = 8 * 16384
+    w = zi_synth.workload("c2")
+    host = gen_numpy(w["spec"], n)
+    pp, pm, pv = (_pinned(a) for a in host[:3])
+    g = to_dev(host[3])
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    zi.zi_engine_set_option(engine, zi.ZI_OPT_SKIP_KERNEL, 1)
+    try:
+        zi.zi_adamw_step_streamed(engine, [(pp, pm, pv, g, lp, n)], zi.ZI_BF16, zi_cfg(w))
+    finally:
+        zi.zi_engine_set_option(engine, zi.ZI_OPT_SKIP_KERNEL, 0)
+    # with the kernel removed the state makes the round trip unchanged
+    assert np.array_equal(pp.numpy(), host[0]) and np.array_equal(pv.numpy(), host[2])
+    assert zi.zi_engine_last_stats(engine).n_kernels == 0
+    src = torch.zeros(1 << 20, dtype=torch.uint8, pin_memory=True)
+    dst = torch.zeros(1 << 20, dtype=torch.uint8, pin_memory=True)
+    for mode in (0, 1, 2):
+        sec = zi.zi_engine_link_probe(engine, src, dst, 1 << 20, mode, 2)
+        assert sec > 0
+
+
+def test_pinned_allocator_round_trip():
+    ptr = zi.zi_pinned_alloc(1 << 20)
+    assert ptr and ptr % 256 == 0
+    assert zi.zi_pinned_free(ptr) == zi.ZI_OK
+
+
+def test_engine_create_destroy_cycle():
+    e = zi.zi_engine_create(0, 4096, 2)
+    assert zi.zi_engine_destroy(e) == zi.ZI_OK
