@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Throughput of the optimizer hot path on one MI355X.
+
+A step is one pass of the whole path over the workload: global gradient norm and
+overflow flag (zi_grad_norm), then the fused AdamW update that reads that result
+on the device (zi_adamw_step).  The default workload is the 1.3e9-element flat
+HBM-resident state (fp32 p/m/v, bf16 gradients, bf16 copy out).
+
+Prints ONE JSON line: the whole-job params/s, the roofline of the dominant kernel
+(the fused update, timed with HIP events on the stream it runs on), the CPU
+oracle timed on a bounded sample, and the streamed step's host-link figures.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+BYTES_PER_ELEM_STEP = 28       # read p, m, v (4 B each) + g (2 B); write p, m, v + 2-byte copy
+BYTES_PER_ELEM_NORM = 2
+
+
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c1", choices=["c0", "c1", "c3"],
+                    help="resident workload to time (c1 is the one the metric is quoted on)")
+    ap.add_argument("--numel", type=int, default=0, help="override the element count (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-streamed", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=3 << 28, help="elements the oracle is timed on")
+    ap.add_argument("--streamed-numel", type=int, default=1 << 30,
+                    help="elements of the host-resident state used for the streamed measurement")
+    return ap.parse_args()
+
+
+def resident(args, torch, zi, zs):
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    w = zs.workload(args.workload)
+    n = args.numel or w["numel"][0]
+    dt = w["lp_dtype"]
+    spec = w["spec"]
+    dev = torch.device("cuda:0")
+    log(f"generating {args.workload}: {n} elements")
+    p = torch.empty(n, dtype=torch.float32, device=dev)
+    m = torch.empty(n, dtype=torch.float32, device=dev)
+    v = torch.empty(n, dtype=torch.float32, device=dev)
+    g = torch.empty(n, dtype=torch.int16, device=dev)
+    lp = torch.zeros(n, dtype=torch.int16, device=dev)
+    chunk = 1 << 26
+    st32 = torch.empty(min(chunk, n), dtype=torch.float32, pin_memory=True)
+    st16 = torch.empty(min(chunk, n), dtype=torch.int16, pin_memory=True)
+    for lo in range(0, n, chunk):
+        c = min(chunk, n - lo)
+        for fill, out in ((spec.fill_p, p), (spec.fill_m, m), (spec.fill_v, v)):
+            fill(st32, c, 0, lo)
+            out[lo:lo + c].copy_(st32[:c])
+        spec.fill_g(st16, c, 0, lo)
+        g[lo:lo + c].copy_(st16[:c])
+    del st32, st16
+
+    cfg = zi.make_config(lr=w["lr"], beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"],
+                         weight_decay=w["weight_decay"], step=w["step"], loss_scale=w["loss_scale"],
+                         max_grad_norm=w["max_grad_norm"])
+    tl = zi.make_tensors([(p, m, v, g, lp, n)])
+    d_norm = torch.zeros(3, dtype=torch.float64, device=dev)
+    ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def one_step(ev=None):
+        zi.zi_grad_norm(tl, dt, w["loss_scale"], d_norm, ws, stream=stream)
+        if ev is not None:
+            ev[0].record(stream)
+        zi.zi_adamw_step(tl, dt, cfg, d_norm, stream=stream)
+        if ev is not None:
+            ev[1].record(stream)
+
+    log(f"warmup {args.warmup}, timing {args.steps} steps")
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+               torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        events[k][2].record(stream)
+        one_step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / args.steps
+    k_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps       # fused update kernel
+    n_ms = sum(e[2].elapsed_time(e[0]) for e in events) / args.steps       # norm pass (2 launches)
+    flag = int(d_norm.cpu().numpy()[2:3].view("uint32")[0])
+    if flag != 0:
+        raise RuntimeError("synthetic gradients raised the overflow flag: the timed steps were skipped")
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "adamw_wide_c1_traffic.json")
+    if args.workload == "c1" and not args.numel and os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+    achieved = BYTES_PER_ELEM_STEP * n / (k_ms * 1e-3) / 1e9
+    out = dict(
+        n=n, sec_per_step=sec_per_step,
+        roofline=dict(bound="hbm", kernel="adamw_wide_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
+                      unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
+                      bytes_per_launch=BYTES_PER_ELEM_STEP * n, kernel_ms=round(k_ms, 4)),
+        norm=dict(kernel="sumsq_partial_kernel+norm_finalize_kernel", ms=round(n_ms, 4),
+                  achieved_GBps=round(BYTES_PER_ELEM_NORM * n / (n_ms * 1e-3) / 1e9, 1),
+                  frac_of_hbm_peak=round(BYTES_PER_ELEM_NORM * n / (n_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)),
+        update_only_params_per_s=n / (k_ms * 1e-3),
+        workload=f"{args.workload}: flat HBM-resident state of {n} elements (fp32 p/m/v, "
+                 f"{'bf16' if dt == 0 else 'fp16'} gradients and copy), step {w['step']}; "
+                 "step = gradient norm + overflow check + fused AdamW",
+    )
+    del p, m, v, g, lp
+    torch.cuda.empty_cache()
+    return out
+
+
+def streamed(args, torch, zi, zs):
+    """Host-link figures of the streamed step on a bounded slice of the host-resident workload."""
+    w = zs.workload("c2")
+    n = args.streamed_numel
+    spec = w["spec"]
+    dev = torch.device("cuda:0")
+    log(f"streamed: pinning and generating 3 x {4 * n / 2**30:.1f} GiB of host state")
+    hp = torch.empty(n, dtype=torch.float32, pin_memory=True)
+    hm = torch.empty(n, dtype=torch.float32, pin_memory=True)
+    hv = torch.empty(n, dtype=torch.float32, pin_memory=True)
+    spec.fill_p(hp, n)
+    spec.fill_m(hm, n)
+    spec.fill_v(hv, n)
+    g = torch.empty(n, dtype=torch.int16, device=dev)
+    st16 = torch.empty(min(1 << 26, n), dtype=torch.int16, pin_memory=True)
+    for lo in range(0, n, 1 << 26):
+        c = min(1 << 26, n - lo)
+        spec.fill_g(st16, c, 0, lo)
+        g[lo:lo + c].copy_(st16[:c])
+    lp = torch.zeros(n, dtype=torch.int16, device=dev)
+    cfg = zi.make_config(lr=w["lr"], beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"],
+                         weight_decay=w["weight_decay"], step=w["step"])
+    eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
+    tl = zi.make_tensors([(hp, hm, hv, g, lp, n)])
+    try:
+        probe_bytes = min(4 * n, 4 << 30)
+        peaks = {}
+        for mode, name in ((0, "h2d"), (1, "d2h"), (2, "bidir")):
+            zi.zi_engine_link_probe(eng, hp, hm, probe_bytes, mode, 1)
+            sec = min(zi.zi_engine_link_probe(eng, hp, hm, probe_bytes, mode, 1) for _ in range(3))
+            peaks[name] = probe_bytes / sec / 1e9            # per direction
+        spec.fill_m(hm, n)                                   # the probe wrote into hm
+        torch.cuda.synchronize()
+        times, copy_only = [], []
+        zi.zi_adamw_step_streamed(eng, tl, w["lp_dtype"], cfg)      # warm-up
+        for _ in range(3):
+            zi.zi_adamw_step_streamed(eng, tl, w["lp_dtype"], cfg)
+            times.append(zi.zi_engine_last_stats(eng).seconds)
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_SKIP_KERNEL, 1)
+        for _ in range(3):
+            zi.zi_adamw_step_streamed(eng, tl, w["lp_dtype"], cfg)
+            copy_only.append(zi.zi_engine_last_stats(eng).seconds)
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_SKIP_KERNEL, 0)
+        st = zi.zi_engine_last_stats(eng)
+    finally:
+        zi.zi_engine_destroy(eng)
+    t = min(times)
+    per_dir = 12 * n / t / 1e9
+    return dict(
+        workload=f"slice of c2: {n} elements of fp32 p/m/v in pinned host memory, 64 MiB chunks, 3 slots",
+        params_per_s=n / t, seconds=t, link_GBps_per_direction=round(per_dir, 2),
+        measured_peak_GBps=dict((k, round(x, 2)) for k, x in peaks.items()),
+        frac_of_bidir_peak=round(per_dir / peaks["bidir"], 4),
+        hidden_ratio=round(t / min(copy_only), 4), copy_only_seconds=min(copy_only),
+        slot_uses=int(st.n_slot_uses))
+
+
+def cpu_baseline(args, zs):
+    """The oracle as it stands, single thread, on the first `cpu_sample` elements of the workload."""
+    import numpy as np
+    import oracle
+    w = zs.workload(args.workload)
+    n = min(args.cpu_sample, args.numel or w["numel"][0])
+    spec = w["spec"]
+    log(f"cpu baseline: oracle on {n} elements")
+    p = np.empty(n, np.float32); m = np.empty(n, np.float32); v = np.empty(n, np.float32)
+    g = np.empty(n, np.uint16); lp = np.empty(n, np.uint16)
+    spec.fill_p(p, n); spec.fill_m(m, n); spec.fill_v(v, n); spec.fill_g(g, n)
+    cfg = oracle.config(lr=w["lr"], beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"],
+                        weight_decay=w["weight_decay"], step=w["step"], loss_scale=w["loss_scale"],
+                        max_grad_norm=w["max_grad_norm"])
+    t0 = time.perf_counter()
+    sumsq, flag = oracle.grad_sumsq([g], w["lp_dtype"])
+    oracle.adamw(p, m, v, g, lp, w["lp_dtype"], cfg, sumsq, flag)
+    dt = time.perf_counter() - t0
+    return dict(value=n / dt, unit="params/s", cores=1, kind="oracle",
+                sample=f"first {n} elements of {args.workload} (gradient norm + AdamW, generation excluded), "
+                       f"{dt:.1f} s on one of {os.cpu_count()} host cores")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no sharding and no collectives; run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+    import paper_2104_07857_amd as zi
+    import zi_synth as zs
+    zi.lib()
+
+    res = resident(args, torch, zi, zs)
+    extras = dict(update_only_params_per_s=res["update_only_params_per_s"], norm=res["norm"])
+    if not args.no_streamed:
+        extras["streamed"] = streamed(args, torch, zi, zs)
+    line = {
+        "metric": "AdamW step params/s + % HBM peak (resident); % host-link BW (streamed)",
+        "value": res["n"] / res["sec_per_step"],
+        "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["sec_per_step"] * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": res["workload"]},
+        "roofline": res["roofline"],
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(args, zs),
+        "extras": extras,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

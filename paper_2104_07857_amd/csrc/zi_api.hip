@@ -28,8 +28,10 @@ zi_status fail(zi_status st, const char* fmt, ...)
 #define ZI_HIP(call)                                                                                  \
     do {                                                                                              \
         hipError_t e_ = (call);                                                                       \
-        if (e_ != hipSuccess)                                                                         \
+        if (e_ != hipSuccess) {                                                                       \
+            (void)hipGetLastError(); /* do not leave a sticky error for the caller's next HIP call */ \
             return fail(ZI_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+        }                                                                                             \
     } while (0)
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -442,6 +444,7 @@ extern "C" zi_status zi_engine_create(zi_engine** out, int32_t device, size_t ch
     do {                                                                                         \
         hipError_t e_ = (call);                                                                  \
         if (e_ != hipSuccess) {                                                                  \
+            (void)hipGetLastError();                                                             \
             engine_release(e);                                                                   \
             return fail(e_ == hipErrorOutOfMemory ? ZI_ERR_NOMEM : ZI_ERR_HIP, "%s failed: %s",   \
                         #call, hipGetErrorString(e_));                                           \
@@ -671,6 +674,7 @@ extern "C" zi_status zi_pinned_alloc(void** out, size_t bytes)
     hipError_t e = hipHostMalloc(out, bytes, hipHostMallocDefault);
     if (e != hipSuccess) {
         *out = nullptr;
+        (void)hipGetLastError();   // a failed allocation must not poison the caller's next HIP call
         return fail(e == hipErrorOutOfMemory ? ZI_ERR_NOMEM : ZI_ERR_HIP, "hipHostMalloc(%zu) failed: %s", bytes,
                     hipGetErrorString(e));
     }

@@ -1,0 +1,264 @@
+"""The five workloads at their full sizes, in the launch configuration bench.py times.
+
+At these sizes the oracle verifies seeded sample ranges (both ends, tile / chunk / 2^32 boundaries,
+random places) that it recomputes from regenerated inputs, plus properties that hold for every
+element: the low-precision copy equals the round-to-nearest-even cast of the stored fp32 parameter
+(checked with the tensor library's own converter over the whole array), and a skipped step leaves
+every bit in place.
+"""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2104_07857_amd as zi
+import zi_synth
+from gpu_util import (NormBuffers, TOL_NORM_REL, compare_state, device_range, device_state, fill_device_f32,
+                      fill_device_lp,
+                      gen_numpy, oracle_cfg, oracle_range, progress, sample_ranges, to_np, zi_cfg)
+
+pytestmark = pytest.mark.gpu
+
+WIDTH = 1 << 16
+
+
+def _lp_torch(dt):
+    return torch.bfloat16 if dt == zi.ZI_BF16 else torch.float16
+
+
+def _copy_matches_cast_everywhere(p_dev, lp_dev, dt, block=1 << 28):
+    n = p_dev.numel()
+    for lo in range(0, n, block):
+        hi = min(lo + block, n)
+        want = p_dev[lo:hi].to(_lp_torch(dt)).view(torch.int16)
+        if not torch.equal(want, lp_dev[lo:hi]):
+            bad = int((want != lp_dev[lo:hi]).sum())
+            raise AssertionError(f"low-precision copy differs from the cast of p in [{lo},{hi}): {bad} elements")
+
+
+def test_c1_resident_1p3e9():
+    w = zi_synth.workload("c1")
+    n, dt, spec = w["numel"][0], w["lp_dtype"], w["spec"]
+    progress(f"c1: generating {n} elements")
+    p, m, v, g, lp = device_state(spec, n)
+    nb = NormBuffers()
+    tl = [(p, m, v, g, lp, n)]
+    zi.zi_grad_norm(tl, dt, w["loss_scale"], nb.out, nb.ws)
+    zi.zi_adamw_step(tl, dt, zi_cfg(w), nb.out)
+    torch.cuda.synchronize()
+    sumsq, norm, flag = nb.read()
+    assert flag == 0
+    # N(0, 1e-3) gradients; the generator truncates to bf16, which shrinks magnitudes by about 0.3%
+    assert abs(norm - 1e-3 * math.sqrt(n)) < 1e-2 * 1e-3 * math.sqrt(n)
+    progress(f"c1: stepped; norm {norm:.5f}")
+    ranges = sample_ranges(n, WIDTH, extra_points=(4096 * 1000, n // 2, 1 << 30), count=10, seed=1)
+    worst = ""
+    for lo, hi in ranges:
+        exp = oracle_range(spec, dt, oracle_cfg(w), lo, hi)
+        worst = compare_state(exp, device_range(p, m, v, lp, lo, hi), dt, f"c1 [{lo},{hi}) ")
+    _copy_matches_cast_everywhere(p, lp, dt)
+    assert bool((v >= 0).all()) and not bool(torch.isnan(p).any())
+    progress(f"c1: {len(ranges)} ranges of {WIDTH} verified; last: {worst}")
+
+
+def test_c3_loss_scaled_fp16_2e9_overflow_then_clip():
+    w = zi_synth.workload("c3")
+    n, dt, spec = w["numel"][0], w["lp_dtype"], w["spec"]
+    progress(f"c3: generating {n} elements")
+    hg = np.empty(n, np.uint16)
+    spec.fill_g(hg, n)
+    p = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    m = torch.empty_like(p)
+    v = torch.empty_like(p)
+    fill_device_f32(lambda b, c, f: spec.fill_p(b, c, 0, f), n, p)
+    fill_device_f32(lambda b, c, f: spec.fill_m(b, c, 0, f), n, m)
+    fill_device_f32(lambda b, c, f: spec.fill_v(b, c, 0, f), n, v)
+    g = torch.from_numpy(hg.view(np.int16)).to("cuda:0")
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    nb = NormBuffers()
+    tl = [(p, m, v, g, lp, n)]
+
+    # run A: +inf at a seeded index; the step must leave all four arrays bit-identical
+    j = zi_synth.pick_index(spec.seed, 0x696E66, n)
+    saved = int(g[j].item())
+    g[j] = 0x7C00
+    p0, m0, v0 = p.clone(), m.clone(), v.clone()
+    zi.zi_grad_norm(tl, dt, w["loss_scale"], nb.out, nb.ws)
+    zi.zi_adamw_step(tl, dt, zi_cfg(w), nb.out)
+    torch.cuda.synchronize()
+    assert nb.read()[2] == 1
+    assert torch.equal(p.view(torch.int32), p0.view(torch.int32))
+    assert torch.equal(m.view(torch.int32), m0.view(torch.int32))
+    assert torch.equal(v.view(torch.int32), v0.view(torch.int32))
+    assert not bool(lp.any())
+    del p0, m0, v0
+    progress(f"c3 run A: +inf at {j}, flag raised, state bit-identical")
+
+    # run B: unscale, global norm, clip to 1, update
+    g[j] = saved
+    zi.zi_grad_norm(tl, dt, w["loss_scale"], nb.out, nb.ws)
+    zi.zi_adamw_step(tl, dt, zi_cfg(w), nb.out)
+    torch.cuda.synchronize()
+    sumsq, norm, flag = nb.read()
+    progress("c3 run B: stepped; oracle sum of squares over 2e9 elements ...")
+    osumsq, oflag = oracle.grad_sumsq([hg], dt)
+    onorm = math.sqrt(osumsq) / w["loss_scale"]
+    assert flag == oflag == 0
+    assert abs(norm - onorm) <= TOL_NORM_REL * onorm
+    assert abs(onorm - 44.72) < 0.1                      # 1e-3 sqrt(2e9)
+    s = oracle.scalars(oracle_cfg(w), osumsq)
+    assert abs(s.clip - 1.0 / (onorm + 1e-6)) < 1e-12 and 0.0222 < s.clip < 0.0225
+    ranges = sample_ranges(n, WIDTH, extra_points=(j, 1 << 30, n // 3), count=8, seed=3)
+    worst = ""
+    for lo, hi in ranges:
+        exp = oracle_range(spec, dt, oracle_cfg(w), lo, hi, sumsq=osumsq, found_inf=0)
+        worst = compare_state(exp, device_range(p, m, v, lp, lo, hi), dt, f"c3 [{lo},{hi}) ")
+    _copy_matches_cast_everywhere(p, lp, dt)
+    progress(f"c3 run B: norm {norm:.6f} (oracle {onorm:.6f}), clip {s.clip:.6f}; "
+             f"{len(ranges)} ranges verified; last: {worst}")
+
+
+class PinnedF32:
+    """fp32 array in pinned host memory from the library's allocator, viewed as numpy."""
+
+    def __init__(self, n):
+        self.n = n
+        self.ptr = zi.zi_pinned_alloc(4 * max(n, 1))
+        self.np = np.ctypeslib.as_array((ctypes.c_float * max(n, 1)).from_address(self.ptr))[:n]
+
+    def free(self):
+        self.np = None
+        zi.zi_pinned_free(self.ptr)
+
+
+def test_c2_streamed_8e9_from_pinned_host():
+    w = zi_synth.workload("c2")
+    n, dt, spec = w["numel"][0], w["lp_dtype"], w["spec"]
+    chunk = w["chunk_bytes"] // 4
+    # The workload asks for 8e9 elements = 96 GB of pinned state.  A host whose driver caps page-locked
+    # memory below that (64 GiB was measured on the test boxes) gets the largest size that fits, which
+    # still crosses the 2^32-element boundary and ends in a partial chunk.
+    hp = hm = hv = None
+    for n in (w["numel"][0], 5_000_000_000):
+        got = []
+        try:
+            progress(f"c2: pinning 3 x {4 * n / 1e9:.0f} GB")
+            for _ in range(3):
+                got.append(PinnedF32(n))
+            hp, hm, hv = got
+            break
+        except zi.ZiError as e:
+            assert e.status == zi.ZI_ERR_NOMEM
+            progress(f"c2: {n} elements do not fit in page-locked memory here ({e.message})")
+            for a in got:
+                a.free()
+    assert hp is not None, "not even 60 GB of page-locked memory"
+    eng = None
+    try:
+        progress("c2: generating host state")
+        piece = 1 << 30
+        for lo in range(0, n, piece):
+            c = min(piece, n - lo)
+            spec.fill_p(hp.np[lo:lo + c], c, 0, lo)
+            spec.fill_m(hm.np[lo:lo + c], c, 0, lo)
+            spec.fill_v(hv.np[lo:lo + c], c, 0, lo)
+            progress(f"c2: host state {lo + c}/{n}")
+        g = torch.empty(n, dtype=torch.int16, device="cuda:0")
+        fill_device_lp(lambda b, c, f: spec.fill_g(b, c, 0, f), n, g)
+        lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+        progress("c2: gradients resident; streaming")
+        eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
+        st = zi.zi_adamw_step_streamed(eng, [(hp.ptr, hm.ptr, hv.ptr, g, lp, n)], dt, zi_cfg(w), None,
+                                       torch.cuda.current_stream())
+        assert st == zi.ZI_OK
+        stats = zi.zi_engine_last_stats(eng)
+        assert stats.n_slot_uses == (n + chunk - 1) // chunk and stats.bytes_h2d == 12 * n == stats.bytes_d2h
+        assert n != 8_000_000_000 or stats.n_slot_uses == 477
+        progress(f"c2: streamed in {stats.seconds:.2f} s = {12 * n / stats.seconds / 1e9:.1f} GB/s per direction")
+        tail0 = (n // chunk) * chunk
+        ranges = sample_ranges(n, WIDTH, extra_points=(chunk, 2 * chunk, 3 * chunk, 100 * chunk, 1 << 32, tail0),
+                               count=8, seed=2)
+        worst = ""
+        for lo, hi in ranges:
+            exp = oracle_range(spec, dt, oracle_cfg(w), lo, hi)
+            got = (hp.np[lo:hi].copy(), hm.np[lo:hi].copy(), hv.np[lo:hi].copy(), to_np(lp[lo:hi]))
+            worst = compare_state(exp, got, dt, f"c2 [{lo},{hi}) ")
+        # every element: the device-resident copy is the cast of the parameter that came back to the host
+        stage = torch.empty(1 << 28, dtype=torch.float32, pin_memory=True)
+        for lo in range(0, n, 1 << 28):
+            c = min(1 << 28, n - lo)
+            stage.numpy()[:c] = hp.np[lo:lo + c]
+            want = stage[:c].to("cuda:0").to(torch.bfloat16).view(torch.int16)
+            assert torch.equal(want, lp[lo:lo + c]), f"copy/cast mismatch in [{lo},{lo + c})"
+        progress(f"c2: {len(ranges)} ranges verified, copy consistent everywhere; last: {worst}")
+    finally:
+        if eng is not None:
+            zi.zi_engine_destroy(eng)
+        for a in (hp, hm, hv):
+            a.free()
+
+
+def test_c4_ragged_transformer_layers_streamed_with_clip():
+    w = zi_synth.workload("c4")
+    numel, dt, spec = w["numel"], w["lp_dtype"], w["spec"]
+    assert len(numel) == 48
+    progress(f"c4: 48 tensors, {sum(numel)} elements, 144 pinned arrays")
+    host, grads, lps, hgs = [], [], [], []
+    eng = None
+    try:
+        for i, n in enumerate(numel):
+            arrs = (PinnedF32(n), PinnedF32(n), PinnedF32(n))
+            host.append(arrs)
+            spec.fill_p(arrs[0].np, n, i)
+            spec.fill_m(arrs[1].np, n, i)
+            spec.fill_v(arrs[2].np, n, i)
+            hg = np.empty(n, np.uint16)
+            spec.fill_g(hg, n, i)
+            hgs.append(hg)
+            grads.append(torch.from_numpy(hg.view(np.int16)).to("cuda:0"))
+            lps.append(torch.zeros(n, dtype=torch.int16, device="cuda:0"))
+            if i % 12 == 11:
+                progress(f"c4: layer {i // 12} generated")
+        nb = NormBuffers()
+        tl = [(a[0].ptr, a[1].ptr, a[2].ptr, g, lp, n) for a, g, lp, n in zip(host, grads, lps, numel)]
+        zi.zi_grad_norm(tl, dt, w["loss_scale"], nb.out, nb.ws)
+        eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
+        st = zi.zi_adamw_step_streamed(eng, tl, dt, zi_cfg(w), nb.out, torch.cuda.current_stream())
+        assert st == zi.ZI_OK
+        stats = zi.zi_engine_last_stats(eng)
+        assert stats.n_slot_uses == 193 and stats.bytes_h2d == 12 * sum(numel)
+        sumsq, norm, flag = nb.read()
+        progress(f"c4: streamed in {stats.seconds:.2f} s; oracle sum of squares over 3.2e9 elements ...")
+        osumsq, oflag = oracle.grad_sumsq(hgs, dt)
+        onorm = math.sqrt(osumsq)
+        assert flag == oflag == 0 and abs(norm - onorm) <= TOL_NORM_REL * onorm
+        assert abs(onorm - 56.76) < 0.57                 # 1e-3 sqrt(3.22e9), bf16-truncated gradients
+        ocfg = oracle_cfg(w)
+        assert 0.0174 < oracle.scalars(ocfg, osumsq).clip < 0.0179
+        worst = ""
+        checked = 0
+        chunk = w["chunk_bytes"] // 4
+        for i, n in enumerate(numel):
+            if n <= 4 * 8192:
+                ranges = [(0, n)]                         # every small tensor in full
+            elif i % 12 in (2, 10) and i // 12 in (0, 3):
+                ranges = sample_ranges(n, WIDTH, extra_points=(chunk, n - chunk), count=2, seed=i)
+            else:
+                ranges = sample_ranges(n, 8192, count=0, seed=i)     # both ends of every large tensor
+            for lo, hi in ranges:
+                exp = oracle_range(spec, dt, ocfg, lo, hi, tensor=i, sumsq=osumsq)
+                got = (host[i][0].np[lo:hi].copy(), host[i][1].np[lo:hi].copy(), host[i][2].np[lo:hi].copy(),
+                       to_np(lps[i][lo:hi]))
+                worst = compare_state(exp, got, dt, f"c4 tensor {i} [{lo},{hi}) ")
+                checked += hi - lo
+        progress(f"c4: norm {norm:.5f} (oracle {onorm:.5f}); {checked} elements verified over 48 tensors; "
+                 f"last: {worst}")
+    finally:
+        if eng is not None:
+            zi.zi_engine_destroy(eng)
+        for arrs in host:
+            for a in arrs:
+                a.free()
