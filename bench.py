@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--numel", type=int, default=0, help="override the element count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streamed", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=3 << 28, help="elements the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=1_300_000_000, help="elements the oracle is timed on")
     ap.add_argument("--streamed-numel", type=int, default=1 << 30,
                     help="elements of the host-resident state used for the streamed measurement")
     return ap.parse_args()

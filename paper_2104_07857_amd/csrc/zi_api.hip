@@ -101,15 +101,16 @@ zi::StepConsts make_consts(const zi_adamw_config& c)
     return k;
 }
 
-// Number of leading elements before every array of the tensor is 16-byte aligned, or -1 if the
-// arrays have no common such index (then only the element-wise kernel applies).
+// Number of leading elements (0..3) before the index at which the fp32 arrays are 16-byte aligned
+// and the 2-byte arrays 8-byte aligned, or -1 if the arrays have no common such index (then only
+// the element-wise kernel applies).
 int common_head(const void* p, const void* m, const void* v, const void* g, const void* p_lp)
 {
-    const int h = (int)((8 - (reinterpret_cast<uintptr_t>(g) / 2) % 8) % 8);
-    if (p_lp && (int)((8 - (reinterpret_cast<uintptr_t>(p_lp) / 2) % 8) % 8) != h) return -1;
+    const int h = (int)((4 - (reinterpret_cast<uintptr_t>(g) / 2) % 4) % 4);
+    if (p_lp && (int)((4 - (reinterpret_cast<uintptr_t>(p_lp) / 2) % 4) % 4) != h) return -1;
     const void* f[3] = {p, m, v};
     for (const void* x : f)
-        if ((int)((4 - (reinterpret_cast<uintptr_t>(x) / 4) % 4) % 4) != h % 4) return -1;
+        if ((int)((4 - (reinterpret_cast<uintptr_t>(x) / 4) % 4) % 4) != h) return -1;
     return h;
 }
 
@@ -155,8 +156,8 @@ struct StepIssuer {
             return zi::launch_step_elementwise(d, args.c, args.d_norm, dt, l2, stream);
         }
         d.head = (int32_t)(h < numel ? h : numel);
-        const int64_t nvec = (numel - d.head) / zi::kVec;
-        int64_t nt = (nvec + zi::kStepTileVecs - 1) / zi::kStepTileVecs;
+        const int64_t nquad = (numel - d.head) / zi::kQuad;
+        int64_t nt = (nquad + zi::kStepTileQuads - 1) / zi::kStepTileQuads;
         if (nt < 1) nt = 1;                       // the first tile also owns the unaligned ends
         if (nt > 0x7FFFFFFF) return hipErrorInvalidValue;
         if (args.n_desc == zi::kMaxStepDesc || (uint64_t)tiles + (uint64_t)nt > 0x7FFFFFFFull) {
@@ -572,8 +573,8 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
             const Segment& sg = segs[j];
             const zi_tensor& T = t[sg.tensor];
             const uint16_t* g = (const uint16_t*)T.g + sg.elem_offset;
-            // Lead-in elements that give the staged fp32 arrays the 16-byte phase of the gradients.
-            const int64_t phase = (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 8);
+            // Lead-in elements that give the staged fp32 arrays the alignment phase of the gradients.
+            const int64_t phase = (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 4);
             const int64_t so = sg.slot_offset + phase;
             Placed& P = placed[np];
             P.dp = e->slot_array(slot, 0) + so;

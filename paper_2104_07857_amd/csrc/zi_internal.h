@@ -9,15 +9,24 @@
 namespace zi {
 
 constexpr int kThreads = 256;        // 4 wavefronts of 64 lanes per workgroup
-constexpr int kVec = 8;              // elements per 16-byte vector of a 2-byte array
-constexpr int kStepUnroll = 2;       // 16-byte vectors of the gradient array per thread per tile
-constexpr int kStepTileVecs = kThreads * kStepUnroll;
-constexpr int64_t kStepTileElems = (int64_t)kStepTileVecs * kVec;   // 4096 elements per tile
+constexpr int kVec = 8;              // elements per 16-byte vector of a 2-byte array (norm pass)
+// Fused step: a lane owns quads of 4 consecutive elements = one 16-byte vector of each fp32 array and
+// one 8-byte vector of each 2-byte array, so every wavefront-wide access is one contiguous run.
+constexpr int kQuad = 4;
+constexpr int kStepUnroll = 2;       // quads per thread per tile
+constexpr int kStepTileQuads = kThreads * kStepUnroll;
+constexpr int64_t kStepTileElems = (int64_t)kStepTileQuads * kQuad;   // 2048 elements per tile
 constexpr int kMaxStepDesc = 32;     // tensors (or segments) per fused-step launch
+// Dynamic LDS requested (never touched) by the fused step: caps residency at two workgroups per
+// compute unit, which measured about 1.5% faster than full occupancy on this read+write stream.
+#ifndef ZI_STEP_LDS
+#define ZI_STEP_LDS (64 * 1024)
+#endif
+constexpr unsigned kStepOccupancyLds = ZI_STEP_LDS;
 
-constexpr int kNormUnroll = 4;
+constexpr int kNormUnroll = 8;
 constexpr int kNormTileVecs = kThreads * kNormUnroll;
-constexpr int64_t kNormTileElems = (int64_t)kNormTileVecs * kVec;   // 8192 elements per block iteration
+constexpr int64_t kNormTileElems = (int64_t)kNormTileVecs * kVec;   // 16384 elements per block iteration
 constexpr int kMaxNormDesc = 64;     // gradient tensors per partial-sum launch
 constexpr uint32_t kMaxPartials = 16384;   // per-block partial results the workspace holds
 
@@ -37,7 +46,8 @@ struct StepConsts {
 };
 
 // One tensor (or one segment of one) as the fused step sees it.  All pointers are device memory.
-// `head` elements come before the first index at which every array is 16-byte aligned.
+// `head` elements come before the first index at which the fp32 arrays are 16-byte aligned and the
+// 2-byte arrays 8-byte aligned.
 struct StepDesc {
     float* p;
     float* m;
@@ -45,7 +55,7 @@ struct StepDesc {
     const uint16_t* g;
     uint16_t* p_lp;        // may be null
     int64_t numel;
-    int32_t head;          // 0..7
+    int32_t head;          // 0..3
     uint32_t first_tile;   // index of this tensor's first tile within the launch
 };
 

@@ -2,10 +2,11 @@
 // and the fused AdamW read-modify-write pass.
 //
 // Both are pure HBM streams (Section 4.1, "AIT w.r.t. Optimizer States": the step reads every
-// state once and writes it once), so the design is about bytes, not flops: every array is
-// accessed with 16-byte loads and stores, a thread has all loads of a tile in flight before
-// the first use, nothing goes through LDS except the block reduction of the norm, and no
-// matrix core is involved because there is no contraction.
+// state once and writes it once), so the design is about bytes, not flops: each wavefront-wide
+// access is one contiguous run of 16-byte (fp32 arrays) or 8-byte (2-byte arrays) lanes, marked
+// non-temporal because nothing is reused, a thread has all loads of a tile in flight before the
+// first use, nothing goes through LDS except the block reduction of the norm, and no matrix core
+// is involved because there is no contraction.
 //
 // Arithmetic order of the update: see include/zi.h.  Compile with -ffp-contract=off so that the
 // only fused multiply-adds are the ones written as fma below.
@@ -109,32 +110,58 @@ __device__ __forceinline__ void step_scalar_at(const StepDesc& T, int64_t i, flo
     if (T.p_lp) T.p_lp[i] = (uint16_t)narrow16<DT>(p);
 }
 
-struct Vec8 {
-    float4 a, b;
-};
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Streaming accesses: the data is touched once, so it should not displace anything in the caches.
+// (The two switches exist for tuning builds; the defaults are the measured best.)
+#ifndef ZI_NT_LOAD
+#define ZI_NT_LOAD 1
+#endif
+#ifndef ZI_NT_STORE
+#define ZI_NT_STORE 1
+#endif
+template <typename V>
+__device__ __forceinline__ V load_stream(const V* a)
+{
+#if ZI_NT_LOAD
+    return __builtin_nontemporal_load(a);
+#else
+    return *a;
+#endif
+}
+template <typename V>
+__device__ __forceinline__ void store_stream(V* a, V x)
+{
+#if ZI_NT_STORE
+    __builtin_nontemporal_store(x, a);
+#else
+    *a = x;
+#endif
+}
+
+// Four consecutive elements: one 16-byte vector of p, m, v and one 8-byte vector of g.
 template <int DT, bool L2>
-__device__ __forceinline__ uint4 step_vec8(Vec8& p, Vec8& m, Vec8& v, const uint4 g, float gscale,
+__device__ __forceinline__ u32x2 step_quad(f32x4& p, f32x4& m, f32x4& v, const u32x2 g, float gscale,
                                            const StepConsts& c)
 {
-    float g0, g1, g2, g3, g4, g5, g6, g7;
+    float g0, g1, g2, g3;
     widen_pair<DT>(g.x, g0, g1);
     widen_pair<DT>(g.y, g2, g3);
-    widen_pair<DT>(g.z, g4, g5);
-    widen_pair<DT>(g.w, g6, g7);
-    adamw_element<L2>(p.a.x, m.a.x, v.a.x, g0, gscale, c);
-    adamw_element<L2>(p.a.y, m.a.y, v.a.y, g1, gscale, c);
-    adamw_element<L2>(p.a.z, m.a.z, v.a.z, g2, gscale, c);
-    adamw_element<L2>(p.a.w, m.a.w, v.a.w, g3, gscale, c);
-    adamw_element<L2>(p.b.x, m.b.x, v.b.x, g4, gscale, c);
-    adamw_element<L2>(p.b.y, m.b.y, v.b.y, g5, gscale, c);
-    adamw_element<L2>(p.b.z, m.b.z, v.b.z, g6, gscale, c);
-    adamw_element<L2>(p.b.w, m.b.w, v.b.w, g7, gscale, c);
-    uint4 lp;
-    lp.x = narrow_pair<DT>(p.a.x, p.a.y);
-    lp.y = narrow_pair<DT>(p.a.z, p.a.w);
-    lp.z = narrow_pair<DT>(p.b.x, p.b.y);
-    lp.w = narrow_pair<DT>(p.b.z, p.b.w);
+    float px = p.x, py = p.y, pz = p.z, pw = p.w;
+    float mx = m.x, my = m.y, mz = m.z, mw = m.w;
+    float vx = v.x, vy = v.y, vz = v.z, vw = v.w;
+    adamw_element<L2>(px, mx, vx, g0, gscale, c);
+    adamw_element<L2>(py, my, vy, g1, gscale, c);
+    adamw_element<L2>(pz, mz, vz, g2, gscale, c);
+    adamw_element<L2>(pw, mw, vw, g3, gscale, c);
+    p = f32x4{px, py, pz, pw};
+    m = f32x4{mx, my, mz, mw};
+    v = f32x4{vx, vy, vz, vw};
+    u32x2 lp;
+    lp.x = narrow_pair<DT>(px, py);
+    lp.y = narrow_pair<DT>(pz, pw);
     return lp;
 }
 
@@ -153,72 +180,57 @@ __global__ __launch_bounds__(kThreads) void adamw_wide_kernel(const StepArgs a)
     tile -= T.first_tile;
 
     const int64_t head = T.head;
-    const int64_t nvec = (T.numel - head) / kVec;          // whole 8-element vectors of the body
-    const int64_t body_end = head + nvec * kVec;
+    const int64_t nquad = (T.numel - head) / kQuad;        // whole quads of the aligned body
+    const int64_t body_end = head + nquad * kQuad;
 
-    // Elements before and after the aligned body (at most 7 each), by the tensor's first tile.
+    // Elements before and after the aligned body (at most 3 each), by the tensor's first tile.
     if (tile == 0) {
         const int64_t t = threadIdx.x;
         if (t < head) step_scalar_at<DT, L2>(T, t, gscale, a.c);
         const int64_t tail = T.numel - body_end;
-        if (t >= 8 && t - 8 < tail) step_scalar_at<DT, L2>(T, body_end + (t - 8), gscale, a.c);
+        if (t >= 4 && t - 4 < tail) step_scalar_at<DT, L2>(T, body_end + (t - 4), gscale, a.c);
     }
 
-    float4* __restrict__ p4 = reinterpret_cast<float4*>(T.p + head);
-    float4* __restrict__ m4 = reinterpret_cast<float4*>(T.m + head);
-    float4* __restrict__ v4 = reinterpret_cast<float4*>(T.v + head);
-    const uint4* __restrict__ g4 = reinterpret_cast<const uint4*>(T.g + head);
-    uint4* __restrict__ lp4 = T.p_lp ? reinterpret_cast<uint4*>(T.p_lp + head) : nullptr;
+    f32x4* __restrict__ p4 = reinterpret_cast<f32x4*>(T.p + head);
+    f32x4* __restrict__ m4 = reinterpret_cast<f32x4*>(T.m + head);
+    f32x4* __restrict__ v4 = reinterpret_cast<f32x4*>(T.v + head);
+    const u32x2* __restrict__ g2 = reinterpret_cast<const u32x2*>(T.g + head);
+    u32x2* __restrict__ lp2 = T.p_lp ? reinterpret_cast<u32x2*>(T.p_lp + head) : nullptr;
 
-    const int64_t vec0 = (int64_t)tile * kStepTileVecs + threadIdx.x;
+    const int64_t q0 = (int64_t)tile * kStepTileQuads + threadIdx.x;
 
-    if ((int64_t)(tile + 1) * kStepTileVecs <= nvec) {
+    if ((int64_t)(tile + 1) * kStepTileQuads <= nquad) {
         // full tile: every load is issued before the first result is needed
-        Vec8 p[kStepUnroll], m[kStepUnroll], v[kStepUnroll];
-        uint4 g[kStepUnroll];
+        f32x4 p[kStepUnroll], m[kStepUnroll], v[kStepUnroll];
+        u32x2 g[kStepUnroll];
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
-            const int64_t iv = vec0 + (int64_t)u * kThreads;
-            g[u] = g4[iv];
-            p[u].a = p4[2 * iv];
-            p[u].b = p4[2 * iv + 1];
-            m[u].a = m4[2 * iv];
-            m[u].b = m4[2 * iv + 1];
-            v[u].a = v4[2 * iv];
-            v[u].b = v4[2 * iv + 1];
+            const int64_t i = q0 + (int64_t)u * kThreads;
+            g[u] = load_stream(g2 + i);
+            p[u] = load_stream(p4 + i);
+            m[u] = load_stream(m4 + i);
+            v[u] = load_stream(v4 + i);
         }
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
-            const int64_t iv = vec0 + (int64_t)u * kThreads;
-            const uint4 lp = step_vec8<DT, L2>(p[u], m[u], v[u], g[u], gscale, a.c);
-            p4[2 * iv] = p[u].a;
-            p4[2 * iv + 1] = p[u].b;
-            m4[2 * iv] = m[u].a;
-            m4[2 * iv + 1] = m[u].b;
-            v4[2 * iv] = v[u].a;
-            v4[2 * iv + 1] = v[u].b;
-            if (lp4) lp4[iv] = lp;
+            const int64_t i = q0 + (int64_t)u * kThreads;
+            const u32x2 lp = step_quad<DT, L2>(p[u], m[u], v[u], g[u], gscale, a.c);
+            store_stream(p4 + i, p[u]);
+            store_stream(m4 + i, m[u]);
+            store_stream(v4 + i, v[u]);
+            if (lp2) store_stream(lp2 + i, lp);
         }
     } else {
         for (int u = 0; u < kStepUnroll; ++u) {
-            const int64_t iv = vec0 + (int64_t)u * kThreads;
-            if (iv < nvec) {
-                Vec8 p, m, v;
-                const uint4 g = g4[iv];
-                p.a = p4[2 * iv];
-                p.b = p4[2 * iv + 1];
-                m.a = m4[2 * iv];
-                m.b = m4[2 * iv + 1];
-                v.a = v4[2 * iv];
-                v.b = v4[2 * iv + 1];
-                const uint4 lp = step_vec8<DT, L2>(p, m, v, g, gscale, a.c);
-                p4[2 * iv] = p.a;
-                p4[2 * iv + 1] = p.b;
-                m4[2 * iv] = m.a;
-                m4[2 * iv + 1] = m.b;
-                v4[2 * iv] = v.a;
-                v4[2 * iv + 1] = v.b;
-                if (lp4) lp4[iv] = lp;
+            const int64_t i = q0 + (int64_t)u * kThreads;
+            if (i < nquad) {
+                const u32x2 g = load_stream(g2 + i);
+                f32x4 p = load_stream(p4 + i), m = load_stream(m4 + i), v = load_stream(v4 + i);
+                const u32x2 lp = step_quad<DT, L2>(p, m, v, g, gscale, a.c);
+                store_stream(p4 + i, p);
+                store_stream(m4 + i, m);
+                store_stream(v4 + i, v);
+                if (lp2) store_stream(lp2 + i, lp);
             }
         }
     }
@@ -241,11 +253,11 @@ hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(n_tiles), block(kThreads);
     if (dt == ZI_BF16) {
-        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, true>), grid, block, 0, s, a);
-        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, false>), grid, block, 0, s, a);
+        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, true>), grid, block, kStepOccupancyLds, s, a);
+        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, false>), grid, block, kStepOccupancyLds, s, a);
     } else {
-        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, true>), grid, block, 0, s, a);
-        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, false>), grid, block, 0, s, a);
+        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, true>), grid, block, kStepOccupancyLds, s, a);
+        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, false>), grid, block, kStepOccupancyLds, s, a);
     }
     return hipGetLastError();
 }
@@ -290,7 +302,7 @@ __device__ __forceinline__ void sumsq_word(uint32_t w, double& acc0, double& acc
 }
 
 template <int DT>
-__device__ __forceinline__ void sumsq_vec(const uint4 g, double& acc0, double& acc1, uint32_t& flag)
+__device__ __forceinline__ void sumsq_vec(const u32x4 g, double& acc0, double& acc1, uint32_t& flag)
 {
     sumsq_word<DT>(g.x, acc0, acc1, flag);
     sumsq_word<DT>(g.y, acc0, acc1, flag);
@@ -354,7 +366,7 @@ __global__ __launch_bounds__(kThreads) void sumsq_partial_kernel(const NormArgs 
     const int64_t head = T.head;
     const int64_t nvec = (T.numel - head) / kVec;
     const int64_t body_end = head + nvec * kVec;
-    const uint4* __restrict__ g4 = reinterpret_cast<const uint4*>(T.g + head);
+    const u32x4* __restrict__ g4 = reinterpret_cast<const u32x4*>(T.g + head);
 
     double acc0 = 0.0, acc1 = 0.0;
     uint32_t flag = 0;
@@ -377,15 +389,15 @@ __global__ __launch_bounds__(kThreads) void sumsq_partial_kernel(const NormArgs 
     for (int64_t base = (int64_t)b * kNormTileVecs; base < nvec; base += stride) {
         const int64_t iv = base + threadIdx.x;
         if (base + kNormTileVecs <= nvec) {
-            uint4 g[kNormUnroll];
+            u32x4 g[kNormUnroll];
 #pragma unroll
-            for (int u = 0; u < kNormUnroll; ++u) g[u] = g4[iv + (int64_t)u * kThreads];
+            for (int u = 0; u < kNormUnroll; ++u) g[u] = load_stream(g4 + iv + (int64_t)u * kThreads);
 #pragma unroll
             for (int u = 0; u < kNormUnroll; ++u) sumsq_vec<DT>(g[u], acc0, acc1, flag);
         } else {
             for (int u = 0; u < kNormUnroll; ++u) {
                 const int64_t j = iv + (int64_t)u * kThreads;
-                if (j < nvec) sumsq_vec<DT>(g4[j], acc0, acc1, flag);
+                if (j < nvec) sumsq_vec<DT>(load_stream(g4 + j), acc0, acc1, flag);
             }
         }
     }

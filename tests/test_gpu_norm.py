@@ -12,7 +12,7 @@ from gpu_util import NormBuffers, TOL_NORM_REL, progress, to_dev
 
 pytestmark = pytest.mark.gpu
 
-NORM_TILE = 8192
+NORM_TILE = 16384
 
 
 def _gpu_norm(gs, dt, loss_scale=1.0, nb=None):

@@ -11,7 +11,7 @@ from gpu_util import (NormBuffers, compare_state, gen_numpy, oracle_cfg, progres
 
 pytestmark = pytest.mark.gpu
 
-TILE = 4096   # elements one workgroup covers
+TILE = 2048   # elements one workgroup covers
 
 
 def _run_both(p, m, v, g, dt, ocfg, zcfg, with_lp=True, use_norm=False, offsets=None):
@@ -244,11 +244,20 @@ def test_every_fp32_pattern_through_the_copy(dt):
         got = to_np(lp)
         # +-inf turns into NaN on both sides (0 * inf in the decay and update terms), like NaN itself
         isnan = ~np.isfinite(bits.view(np.float32))
-        bad += int((want[~isnan] != got[~isnan]).sum())
+        if c == 0x80000000:
+            want[0] = 0          # the parameter -0 comes back as +0 (see below), and so does its copy
+        wrong = np.flatnonzero((want != got) & ~isnan)
+        if wrong.size:
+            progress("cast mismatches: " + ", ".join(
+                f"p={bits[i]:#010x} want={want[i]:#06x} got={got[i]:#06x}" for i in wrong[:8]))
+        bad += int(wrong.size)
         bad += int((~is_nan_lp(got[isnan], dt)).sum())
-        # p itself: unchanged for every finite or infinite pattern (a -0 may come back as +0)
+        # p itself: unchanged for every finite pattern (a -0 comes back as +0)
         pb = p.view(torch.int32).cpu().numpy().view(np.uint32)
         same = (pb == bits) | ((bits == 0x80000000) & (pb == 0)) | isnan
+        if not same.all():
+            progress("parameter changed: " + ", ".join(
+                f"p={bits[i]:#010x} -> {pb[i]:#010x}" for i in np.flatnonzero(~same)[:8]))
         bad += int((~same).sum())
         if c % (1 << 30) == 0:
             progress(f"cast sweep dt={dt}: {c >> 27}/32 chunks, mismatches so far {bad}")
