@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streamed", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1_300_000_000, help="elements the oracle is timed on")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="only run a plain device copy of 1 GiB five times (scales rocprofv3 byte counters)")
     ap.add_argument("--streamed-numel", type=int, default=1 << 30,
                     help="elements of the host-resident state used for the streamed measurement")
     return ap.parse_args()
@@ -106,10 +108,14 @@ def resident(args, torch, zi, zs):
     if flag != 0:
         raise RuntimeError("synthetic gradients raised the overflow flag: the timed steps were skipped")
 
+    # HBM bytes per launch from hardware counters (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+    # copy kernel of known size): measured offline on this workload, recorded with its commands.
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "adamw_wide_c1_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "adamw_wide_kernel_c1_hbm_traffic.txt")
     if args.workload == "c1" and not args.numel and os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        for ln in open(tpath):
+            if ln.startswith("traffic_bytes_per_launch"):
+                traffic = int(ln.split("=")[1])
     achieved = BYTES_PER_ELEM_STEP * n / (k_ms * 1e-3) / 1e9
     out = dict(
         n=n, sec_per_step=sec_per_step,
@@ -219,6 +225,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (no CPU fallback exists)", file=sys.stderr)
         sys.exit(2)
+    if args.pmc_calibration:
+        # A copy kernel of known size: reads 2^30 bytes and writes 2^30 bytes per launch.
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "5 device copies", "bytes_read_per_launch": 1 << 30,
+                          "bytes_written_per_launch": 1 << 30}), flush=True)
+        return
     import paper_2104_07857_amd as zi
     import zi_synth as zs
     zi.lib()
