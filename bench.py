@@ -117,6 +117,21 @@ def resident(args, torch, zi, zs):
             if ln.startswith("traffic_bytes_per_launch"):
                 traffic = int(ln.split("=")[1])
     achieved = BYTES_PER_ELEM_STEP * n / (k_ms * 1e-3) / 1e9
+
+    # Practical ceilings of this device, same run, same buffers: a pure read, a 1:1 copy and an
+    # in-place update with the fused step's access shape and no arithmetic.
+    ceil = {}
+    nbytes = 4 * (n - n % 4)
+    for mode, name, moved in ((0, "read", nbytes), (1, "copy", 2 * nbytes), (2, "update_in_place", 2 * nbytes)):
+        ts = []
+        for _ in range(7):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            zi.zi_hbm_probe(p, m, nbytes, mode, stream)
+            b.record(stream)
+            b.synchronize()
+            ts.append(a.elapsed_time(b))
+        ceil[name + "_GBps"] = round(moved / (sorted(ts)[len(ts) // 2] * 1e-3) / 1e9, 1)
     out = dict(
         n=n, sec_per_step=sec_per_step,
         roofline=dict(bound="hbm", kernel="adamw_wide_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
@@ -126,6 +141,8 @@ def resident(args, torch, zi, zs):
                   achieved_GBps=round(BYTES_PER_ELEM_NORM * n / (n_ms * 1e-3) / 1e9, 1),
                   frac_of_hbm_peak=round(BYTES_PER_ELEM_NORM * n / (n_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)),
         update_only_params_per_s=n / (k_ms * 1e-3),
+        hbm_ceilings=dict(ceil, fused_step_frac_of_copy=round(achieved / ceil["copy_GBps"], 4),
+                          norm_frac_of_read=round(BYTES_PER_ELEM_NORM * n / (n_ms * 1e-3) / 1e9 / ceil["read_GBps"], 4)),
         workload=f"{args.workload}: flat HBM-resident state of {n} elements (fp32 p/m/v, "
                  f"{'bf16' if dt == 0 else 'fp16'} gradients and copy), step {w['step']}; "
                  "step = gradient norm + overflow check + fused AdamW",
@@ -240,7 +257,8 @@ def main():
     zi.lib()
 
     res = resident(args, torch, zi, zs)
-    extras = dict(update_only_params_per_s=res["update_only_params_per_s"], norm=res["norm"])
+    extras = dict(update_only_params_per_s=res["update_only_params_per_s"], norm=res["norm"],
+                  hbm_ceilings=res["hbm_ceilings"])
     if not args.no_streamed:
         extras["streamed"] = streamed(args, torch, zi, zs)
     line = {

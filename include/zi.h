@@ -56,10 +56,11 @@
  *     buffer untouched unless stated otherwise.  Nothing throws or aborts.
  *     zi_last_error() gives the text of the calling thread's last error.
  *   - Pointers must be aligned to their element size (4 bytes for p/m/v, 2
- *     bytes for g and p_lp).  16-byte alignment of all arrays of a tensor, or
- *     any common misalignment (all arrays offset by the same number of
- *     elements from a 16-byte boundary), takes the wide path; any other
- *     placement takes a slower element-wise path with identical results.
+ *     bytes for g and p_lp).  The wide path needs an element index at which
+ *     the fp32 arrays are 16-byte aligned and the 2-byte arrays 8-byte aligned:
+ *     true for aligned arrays and for any common misalignment (all arrays
+ *     offset by the same number of elements, modulo 4).  Any other placement
+ *     takes a slower element-wise path with identical results.
  *   - numel == 0 and n_tensors == 0 are valid and do nothing.
  *   - The library is gfx950-only and has no CPU fallback: without a usable HIP
  *     device every compute call returns ZI_ERR_HIP.
@@ -237,6 +238,16 @@ typedef struct {
 
 zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems, zi_chunk_segment* out,
                          int64_t cap, int64_t* n_segments_out, int64_t* n_slot_uses_out);
+
+/*
+ * HBM stream probe (a measurement aid): one launch with the fused step's access shape and no
+ * arithmetic, over `bytes` (positive multiple of 16) of 16-byte aligned device memory.
+ * mode 0 = read d_a; mode 1 = copy d_a to d_b (non-overlapping); mode 2 = update d_a in place
+ * (every fp32 value + 1).  Asynchronous on hip_stream.  Timing it gives the bandwidth a pure
+ * read, a 1:1 copy and an in-place read-modify-write reach on this device, i.e. the practical
+ * ceilings of the norm pass and of the fused step.
+ */
+zi_status zi_hbm_probe(void* d_a, void* d_b, size_t bytes, int32_t mode, void* hip_stream);
 
 /* Pinned (page-locked, device-visible) host memory.  zi_pinned_free(NULL) is accepted. */
 zi_status zi_pinned_alloc(void** out, size_t bytes);

@@ -29,7 +29,7 @@ ZI_OPT_SKIP_KERNEL = 0
 EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
-    "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free",
+    "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
 ]
 
 
@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.zi_plan_chunks.restype = ctypes.c_int
         L.zi_plan_chunks.argtypes = [ctypes.POINTER(i64), i32, i64, ctypes.POINTER(zi_chunk_segment), i64,
                                      ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.zi_hbm_probe.restype = ctypes.c_int
+        L.zi_hbm_probe.argtypes = [vp, vp, sz, i32, vp]
         L.zi_pinned_alloc.restype = ctypes.c_int
         L.zi_pinned_alloc.argtypes = [ctypes.POINTER(vp), sz]
         L.zi_pinned_free.restype = ctypes.c_int
@@ -236,6 +238,10 @@ def zi_plan_chunks(numel: Sequence[int], chunk_elems: int):
     out = (zi_chunk_segment * max(nseg.value, 1))()
     _check(lib().zi_plan_chunks(arr, n, int(chunk_elems), out, nseg.value, ctypes.byref(nseg), ctypes.byref(nuse)))
     return [out[i] for i in range(nseg.value)], nuse.value
+
+
+def zi_hbm_probe(d_a, d_b, nbytes: int, mode: int, stream=None) -> int:
+    return _check(lib().zi_hbm_probe(_addr(d_a), _addr(d_b), int(nbytes), int(mode), _stream(stream)))
 
 
 def zi_pinned_alloc(nbytes: int) -> int:

@@ -459,4 +459,36 @@ hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, flo
     return hipGetLastError();
 }
 
+// -------------------------------------------------------------- plain streams (measurement aid)
+
+// The same access shape as the fused step (one 16-byte vector per lane, non-temporal, one short
+// tile per workgroup) with no arithmetic: what the memory system gives a pure read, a 1:1 copy and
+// an in-place read-modify-write.  These are the ceilings the fused step is compared with.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void hbm_probe_kernel(f32x4* __restrict__ a, f32x4* __restrict__ b, int64_t n4,
+                                                            float* sink)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n4) return;
+    f32x4 x = load_stream(a + i);
+    if constexpr (MODE == 0) {
+        if (x.x + x.y + x.z + x.w == 1.2345678e-30f) *sink = 1.0f;   // keeps the load alive
+    } else if constexpr (MODE == 1) {
+        store_stream(b + i, x);
+    } else {
+        x += 1.0f;
+        store_stream(a + i, x);
+    }
+}
+
+hipError_t launch_hbm_probe(void* a, void* b, int64_t n4, int mode, float* sink, hipStream_t s)
+{
+    if (n4 <= 0) return hipSuccess;
+    const dim3 grid((uint32_t)((n4 + kThreads - 1) / kThreads)), block(kThreads);
+    if (mode == 0) hipLaunchKernelGGL(hbm_probe_kernel<0>, grid, block, 0, s, (f32x4*)a, (f32x4*)b, n4, sink);
+    else if (mode == 1) hipLaunchKernelGGL(hbm_probe_kernel<1>, grid, block, 0, s, (f32x4*)a, (f32x4*)b, n4, sink);
+    else hipLaunchKernelGGL(hbm_probe_kernel<2>, grid, block, 0, s, (f32x4*)a, (f32x4*)b, n4, sink);
+    return hipGetLastError();
+}
+
 }  // namespace zi

@@ -20,7 +20,7 @@ def _declared_functions():
 
 def test_library_exports_every_declared_symbol():
     declared = _declared_functions()
-    assert len(declared) >= 13
+    assert len(declared) >= 14
     L = ctypes.CDLL(zi.LIB_PATH)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in include/zi.h but not exported"
@@ -129,6 +129,14 @@ def test_engine_and_misc_argument_checks():
         zi.zi_engine_last_stats(None)
     with pytest.raises(zi.ZiError):
         zi.zi_engine_set_option(None, 0, 1)
+    buf = np.zeros(64, np.float32)
+    for args in ((buf, buf, 256, 3), (None, buf, 256, 0), (buf, None, 256, 1), (buf, buf, 0, 0), (buf, buf, 100, 0)):
+        with pytest.raises(zi.ZiError) as e:
+            zi.zi_hbm_probe(*args)
+        assert e.value.status == zi.ZI_ERR_INVALID_ARG
+    with pytest.raises(zi.ZiError) as e:
+        zi.zi_hbm_probe(buf.ctypes.data + 4, buf, 64, 0)
+    assert e.value.status == zi.ZI_ERR_ALIGNMENT
 
 
 def _check_plan(numel, chunk):

@@ -103,3 +103,19 @@ def test_constant_closed_form():
     sumsq, norm, flag = _gpu_norm([g], zi.ZI_BF16, loss_scale=2.0)
     assert sumsq == 0.0625 * (1 << 22) and norm == 0.25 * 2048 / 2.0 and flag == 0
     progress("norm closed form ok")
+
+
+def test_hbm_probe_modes_do_what_they_say():
+    n = (1 << 20) + 4
+    a = torch.arange(n, dtype=torch.float32, device="cuda:0")
+    b = torch.zeros(n + 4, dtype=torch.float32, device="cuda:0")
+    ref = a.clone()
+    zi.zi_hbm_probe(a, None, 4 * n, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(a, ref)                       # a read leaves the buffer alone
+    zi.zi_hbm_probe(a, b, 4 * n, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(b[:n], ref) and not bool(b[n:].any())
+    zi.zi_hbm_probe(a, None, 4 * n, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(a, ref + 1.0)
