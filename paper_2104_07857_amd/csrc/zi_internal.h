@@ -13,14 +13,16 @@ constexpr int kVec = 8;              // elements per 16-byte vector of a 2-byte 
 // Fused step: a lane owns quads of 4 consecutive elements = one 16-byte vector of each fp32 array and
 // one 8-byte vector of each 2-byte array, so every wavefront-wide access is one contiguous run.
 constexpr int kQuad = 4;
+constexpr int kStepThreads = 64;     // one wavefront per workgroup
 constexpr int kStepUnroll = 2;       // quads per thread per tile
-constexpr int kStepTileQuads = kThreads * kStepUnroll;
-constexpr int64_t kStepTileElems = (int64_t)kStepTileQuads * kQuad;   // 2048 elements per tile
+constexpr int kStepTileQuads = kStepThreads * kStepUnroll;
+constexpr int64_t kStepTileElems = (int64_t)kStepTileQuads * kQuad;   // 512 elements per tile
 constexpr int kMaxStepDesc = 32;     // tensors (or segments) per fused-step launch
-// Dynamic LDS requested (never touched) by the fused step: caps residency at two workgroups per
-// compute unit, which measured about 1.5% faster than full occupancy on this read+write stream.
+// Dynamic LDS requested (never touched) by the fused step: caps residency at eight single-wavefront
+// workgroups per compute unit.  On this 1:1 read/write stream few, short-lived wavefronts measured
+// 4-8% faster than full occupancy (sweeps over workgroup size, unroll and residency).
 #ifndef ZI_STEP_LDS
-#define ZI_STEP_LDS (64 * 1024)
+#define ZI_STEP_LDS (20 * 1024)
 #endif
 constexpr unsigned kStepOccupancyLds = ZI_STEP_LDS;
 

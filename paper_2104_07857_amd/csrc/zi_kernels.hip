@@ -168,7 +168,7 @@ __device__ __forceinline__ u32x2 step_quad(f32x4& p, f32x4& m, f32x4& v, const u
 // One workgroup = one tile of kStepTileElems elements of one tensor.  blockIdx.x counts tiles over
 // all tensors of the launch; first_tile locates the tensor.
 template <int DT, bool L2>
-__global__ __launch_bounds__(kThreads) void adamw_wide_kernel(const StepArgs a)
+__global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs a)
 {
     float gscale;
     if (!step_prologue(a.d_norm, a.c, gscale)) return;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kThreads) void adamw_wide_kernel(const StepArgs a)
         u32x2 g[kStepUnroll];
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
-            const int64_t i = q0 + (int64_t)u * kThreads;
+            const int64_t i = q0 + (int64_t)u * kStepThreads;
             g[u] = load_stream(g2 + i);
             p[u] = load_stream(p4 + i);
             m[u] = load_stream(m4 + i);
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void adamw_wide_kernel(const StepArgs a)
         }
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
-            const int64_t i = q0 + (int64_t)u * kThreads;
+            const int64_t i = q0 + (int64_t)u * kStepThreads;
             const u32x2 lp = step_quad<DT, L2>(p[u], m[u], v[u], g[u], gscale, a.c);
             store_stream(p4 + i, p[u]);
             store_stream(m4 + i, m[u]);
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void adamw_wide_kernel(const StepArgs a)
         }
     } else {
         for (int u = 0; u < kStepUnroll; ++u) {
-            const int64_t i = q0 + (int64_t)u * kThreads;
+            const int64_t i = q0 + (int64_t)u * kStepThreads;
             if (i < nquad) {
                 const u32x2 g = load_stream(g2 + i);
                 f32x4 p = load_stream(p4 + i), m = load_stream(m4 + i), v = load_stream(v4 + i);
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(kThreads) void adamw_elementwise_kernel(const StepD
 hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2, hipStream_t s)
 {
     if (n_tiles == 0) return hipSuccess;
-    const dim3 grid(n_tiles), block(kThreads);
+    const dim3 grid(n_tiles), block(kStepThreads);
     if (dt == ZI_BF16) {
         if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, true>), grid, block, kStepOccupancyLds, s, a);
         else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, false>), grid, block, kStepOccupancyLds, s, a);

@@ -11,7 +11,7 @@ from gpu_util import (NormBuffers, compare_state, gen_numpy, oracle_cfg, progres
 
 pytestmark = pytest.mark.gpu
 
-TILE = 2048   # elements one workgroup covers
+TILE = 512    # elements one workgroup covers
 
 
 def _run_both(p, m, v, g, dt, ocfg, zcfg, with_lp=True, use_norm=False, offsets=None):
