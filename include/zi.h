@@ -171,7 +171,8 @@ zi_status zi_engine_create(zi_engine** out, int32_t device, size_t chunk_bytes_p
 zi_status zi_engine_destroy(zi_engine* e);   /* NULL is accepted */
 
 /*
- * AdamW step with p, m, v in PINNED HOST memory and g, p_lp in device memory
+ * AdamW step with p, m, v in PINNED HOST memory (or ordinary host memory if the
+ * engine has a pinned ring, see zi_engine_set_option) and g, p_lp in device memory
  * (Section 5.2.2: the state is brought to the faster memory in chunks, one chunk
  * at a time, and written back, with reads, writes and compute overlapped).
  * Tensors larger than a chunk are split on chunk boundaries; consecutive small
@@ -195,16 +196,29 @@ typedef struct {
     int64_t n_slot_uses;       /* chunk-slots processed */
     int64_t n_copies;          /* hipMemcpyAsync calls issued */
     int64_t n_kernels;         /* kernel launches */
+    uint64_t bytes_staged_host; /* bytes copied by CPU threads through the pinned ring (both ways) */
 } zi_stream_stats;
 
 zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
 
 /*
- * Engine options.  ZI_OPT_SKIP_KERNEL = 1 runs the identical copy pipeline
- * without launching the update (a measurement aid: the time of the pipeline
- * with the update removed).  Default 0.
+ * Engine options.
+ * ZI_OPT_SKIP_KERNEL = 1 runs the identical copy pipeline without launching the
+ * update (a measurement aid: the time of the pipeline with the update removed).
+ * ZI_OPT_HOST_RING_SLOTS = n gives the engine a ring of n pinned host slots
+ * (each 3 arrays of the chunk size) and two small CPU thread pools.  With it,
+ * zi_adamw_step_streamed also accepts p, m, v in ORDINARY (pageable) host
+ * memory: each chunk is copied into a ring slot by CPU threads, moved to HBM
+ * and back by the copy engines, and copied out again, all stages overlapped
+ * (Section 6.3, pinned memory management layer: a small reused pinned pool
+ * serves model states far larger than what can be page-locked).  Results are
+ * bit-identical to the pinned path.  Without a ring, pageable state is refused.
  */
-typedef enum { ZI_OPT_SKIP_KERNEL = 0 } zi_engine_option;
+typedef enum {
+    ZI_OPT_SKIP_KERNEL = 0,
+    ZI_OPT_HOST_RING_SLOTS = 1,    /* 0 = none (default); 2..16: allocate a pinned ring of that many slots */
+    ZI_OPT_HOST_COPY_THREADS = 2   /* 1..64 CPU threads per direction for the ring (default 6) */
+} zi_engine_option;
 zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t value);
 
 /*

@@ -25,6 +25,8 @@ ZI_FP16 = 1
 ZI_MODE_ADAMW = 0
 ZI_MODE_ADAM_L2 = 1
 ZI_OPT_SKIP_KERNEL = 0
+ZI_OPT_HOST_RING_SLOTS = 1
+ZI_OPT_HOST_COPY_THREADS = 2
 
 EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
@@ -58,7 +60,8 @@ class zi_tensor(ctypes.Structure):
 
 class zi_stream_stats(ctypes.Structure):
     _fields_ = [("seconds", ctypes.c_double), ("bytes_h2d", ctypes.c_uint64), ("bytes_d2h", ctypes.c_uint64),
-                ("n_slot_uses", ctypes.c_int64), ("n_copies", ctypes.c_int64), ("n_kernels", ctypes.c_int64)]
+                ("n_slot_uses", ctypes.c_int64), ("n_copies", ctypes.c_int64), ("n_kernels", ctypes.c_int64),
+                ("bytes_staged_host", ctypes.c_uint64)]
 
 
 class zi_chunk_segment(ctypes.Structure):

@@ -2,7 +2,11 @@
 // pinned-host <-> HBM streaming engine.  See include/zi.h for the contract of every call.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <chrono>
+#include <condition_variable>
+#include <mutex>
+#include <thread>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -364,7 +368,96 @@ extern "C" zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int
 
 // ============================================================================ streaming engine
 
+namespace {
+
+// A few threads that copy a list of (dst, src, bytes) pieces between ordinary host memory and the
+// pinned ring.  run() blocks until the whole list is copied; the calling thread takes part.
+class CopyPool {
+public:
+    struct Piece { char* dst; const char* src; size_t bytes; };
+
+    explicit CopyPool(int n_threads)
+    {
+        for (int i = 1; i < n_threads; ++i) workers_.emplace_back([this] { loop(); });
+    }
+    ~CopyPool()
+    {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            stop_ = true;
+        }
+        cv_job_.notify_all();
+        for (auto& w : workers_) w.join();
+    }
+    void run(const std::vector<Piece>& pieces)
+    {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            pieces_ = &pieces;
+            next_.store(0);
+            pending_ = (int)workers_.size();
+            ++generation_;
+        }
+        cv_job_.notify_all();
+        drain();
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_done_.wait(lk, [this] { return pending_ == 0; });
+        pieces_ = nullptr;
+    }
+
+private:
+    void drain()
+    {
+        const std::vector<Piece>& ps = *pieces_;
+        for (size_t i = next_.fetch_add(1); i < ps.size(); i = next_.fetch_add(1))
+            std::memcpy(ps[i].dst, ps[i].src, ps[i].bytes);
+    }
+    void loop()
+    {
+        uint64_t seen = 0;
+        for (;;) {
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_job_.wait(lk, [&] { return stop_ || generation_ != seen; });
+                if (stop_) return;
+                seen = generation_;
+            }
+            drain();
+            {
+                std::lock_guard<std::mutex> lk(mu_);
+                --pending_;
+            }
+            cv_done_.notify_one();
+        }
+    }
+    std::vector<std::thread> workers_;
+    std::mutex mu_;
+    std::condition_variable cv_job_, cv_done_;
+    const std::vector<Piece>* pieces_ = nullptr;
+    std::atomic<size_t> next_{0};
+    uint64_t generation_ = 0;
+    int pending_ = 0;
+    bool stop_ = false;
+};
+
+constexpr int kMaxHostSlots = 16;
+constexpr size_t kCopyPieceBytes = 4u << 20;
+
+}  // namespace
+
 struct zi_engine {
+    // Pinned ring for state that lives in ordinary (pageable) host memory: n_hslots slots shaped like
+    // the HBM slots, filled and emptied by two small thread pools.
+    int n_hslots = 0;
+    char* hring = nullptr;
+    hipEvent_t ev_back[kMaxHostSlots] = {};
+    int copy_threads = 6;
+    CopyPool* pool_in = nullptr;
+    CopyPool* pool_out = nullptr;
+    float* hslot_array(int hslot, int which) const
+    {
+        return reinterpret_cast<float*>(hring + ((size_t)hslot * 3 + which) * array_bytes);
+    }
     int device = 0;
     size_t chunk_bytes = 0;
     int64_t chunk_elems = 0;
@@ -396,6 +489,20 @@ zi_status check_engine(const zi_engine* e)
     return ZI_OK;
 }
 
+void ring_release(zi_engine* e)
+{
+    delete e->pool_in;
+    delete e->pool_out;
+    e->pool_in = e->pool_out = nullptr;
+    for (int i = 0; i < kMaxHostSlots; ++i) {
+        if (e->ev_back[i]) (void)hipEventDestroy(e->ev_back[i]);
+        e->ev_back[i] = nullptr;
+    }
+    if (e->hring) (void)hipHostFree(e->hring);
+    e->hring = nullptr;
+    e->n_hslots = 0;
+}
+
 void engine_release(zi_engine* e)
 {
     for (int i = 0; i < 8; ++i) {
@@ -410,6 +517,7 @@ void engine_release(zi_engine* e)
     if (e->s_d2h) (void)hipStreamDestroy(e->s_d2h);
     if (e->staging) (void)hipFree(e->staging);
     if (e->h_norm) (void)hipHostFree(e->h_norm);
+    ring_release(e);
     e->magic = 0;
     delete e;
 }
@@ -497,6 +605,48 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
         e->skip_kernel = value != 0;
         return ZI_OK;
     }
+    if (option == ZI_OPT_HOST_COPY_THREADS) {
+        if (value < 1 || value > 64) return fail(ZI_ERR_INVALID_ARG, "host copy threads must be in 1..64");
+        e->copy_threads = (int)value;
+        if (e->pool_in) {
+            delete e->pool_in;
+            delete e->pool_out;
+            e->pool_in = new (std::nothrow) CopyPool(e->copy_threads);
+            e->pool_out = new (std::nothrow) CopyPool(e->copy_threads);
+            if (!e->pool_in || !e->pool_out) return fail(ZI_ERR_NOMEM, "out of host memory");
+        }
+        return ZI_OK;
+    }
+    if (option == ZI_OPT_HOST_RING_SLOTS) {
+        if (value != 0 && (value < 2 || value > kMaxHostSlots))
+            return fail(ZI_ERR_INVALID_ARG, "host ring slots must be 0 or in 2..%d", kMaxHostSlots);
+        ZI_HIP(hipSetDevice(e->device));
+        ring_release(e);
+        if (value == 0) return ZI_OK;
+        hipError_t he = hipHostMalloc((void**)&e->hring, (size_t)value * 3 * e->array_bytes, hipHostMallocDefault);
+        if (he != hipSuccess) {
+            e->hring = nullptr;
+            (void)hipGetLastError();
+            return fail(he == hipErrorOutOfMemory ? ZI_ERR_NOMEM : ZI_ERR_HIP, "pinned ring of %lld slots: %s",
+                        (long long)value, hipGetErrorString(he));
+        }
+        for (int i = 0; i < (int)value; ++i) {
+            he = hipEventCreateWithFlags(&e->ev_back[i], hipEventDisableTiming);
+            if (he != hipSuccess) {
+                (void)hipGetLastError();
+                ring_release(e);
+                return fail(ZI_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(he));
+            }
+        }
+        e->pool_in = new (std::nothrow) CopyPool(e->copy_threads);
+        e->pool_out = new (std::nothrow) CopyPool(e->copy_threads);
+        if (!e->pool_in || !e->pool_out) {
+            ring_release(e);
+            return fail(ZI_ERR_NOMEM, "out of host memory");
+        }
+        e->n_hslots = (int)value;
+        return ZI_OK;
+    }
     return fail(ZI_ERR_INVALID_ARG, "unknown engine option %d", option);
 }
 
@@ -514,8 +664,10 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
     hipStream_t user = (hipStream_t)hip_stream;
     e->stats = zi_stream_stats{};
 
-    // The state must be page-locked: a pageable source would turn every copy into a staged,
-    // synchronous one and the pipeline would silently serialise.
+    // State that is not page-locked cannot feed the copy engines directly (a pageable source turns
+    // every copy into a staged, synchronous one).  It goes through the engine's pinned ring if one
+    // has been set up, otherwise it is refused.
+    bool pageable = false;
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (t[i].numel == 0) continue;
         const void* arrs[3] = {t[i].p, t[i].m, t[i].v};
@@ -524,7 +676,13 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
             hipError_t pe = hipPointerGetAttributes(&attr, a);
             if (pe != hipSuccess || attr.type != hipMemoryTypeHost) {
                 (void)hipGetLastError();
-                return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be pinned host memory", i);
+                if (pe == hipSuccess && attr.type != hipMemoryTypeUnregistered)
+                    return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be host memory", i);
+                if (e->n_hslots == 0)
+                    return fail(ZI_ERR_INVALID_ARG,
+                                "tensor %d: p, m, v must be pinned host memory (or give the engine a pinned "
+                                "ring with ZI_OPT_HOST_RING_SLOTS)", i);
+                pageable = true;
             }
         }
     }
@@ -553,80 +711,202 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
 
     const zi::StepConsts k = make_consts(*cfg);
     const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
-    const auto t0 = std::chrono::steady_clock::now();
+    const int n_h = e->n_hslots;
 
-    size_t si = 0;
-    for (int64_t use = 0; use < n_uses; ++use) {
-        const int slot = (int)(use % e->n_slots);
-        // Slot reuse is ordered by the event of the device-to-host copies that last emptied it.
-        // Waiting for the OLDEST slot use keeps the host n_slots uses ahead of the copy engines.
-        if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_d2h[slot]));
+    // First segment of every slot use.
+    std::vector<size_t> use_begin((size_t)n_uses + 1, segs.size());
+    for (size_t j = segs.size(); j-- > 0;) use_begin[(size_t)segs[j].slot_use] = j;
+    for (int64_t u = n_uses - 1; u >= 0; --u)
+        if (use_begin[(size_t)u] > use_begin[(size_t)u + 1]) use_begin[(size_t)u] = use_begin[(size_t)u + 1];
 
-        const size_t s_begin = si;
-        while (si < segs.size() && segs[si].slot_use == use) ++si;
-
-        struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes; };
-        Placed placed[zi::kMaxStepDesc];
-        StepIssuer issue(k, d_norm, (int)dt, l2, e->s_k);
-        int np = 0;
-        for (size_t j = s_begin; j < si; ++j, ++np) {
+    // Where a segment sits inside a slot (HBM slot and pinned-ring slot share one layout).
+    auto slot_off = [&](const Segment& sg) -> int64_t {
+        const uint16_t* g = (const uint16_t*)t[sg.tensor].g + sg.elem_offset;
+        // Lead-in elements that give the staged fp32 arrays the alignment phase of the gradients.
+        return sg.slot_offset + (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 4);
+    };
+    // Copy lists between the caller's ordinary memory and ring slot h for one slot use.
+    auto ring_pieces = [&](int64_t use, int h, bool inbound, std::vector<CopyPool::Piece>& out) {
+        out.clear();
+        for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
             const Segment& sg = segs[j];
             const zi_tensor& T = t[sg.tensor];
-            const uint16_t* g = (const uint16_t*)T.g + sg.elem_offset;
-            // Lead-in elements that give the staged fp32 arrays the alignment phase of the gradients.
-            const int64_t phase = (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 4);
-            const int64_t so = sg.slot_offset + phase;
-            Placed& P = placed[np];
-            P.dp = e->slot_array(slot, 0) + so;
-            P.dm = e->slot_array(slot, 1) + so;
-            P.dv = e->slot_array(slot, 2) + so;
-            P.hp = (char*)T.p + sg.elem_offset * 4;
-            P.hm = (char*)T.m + sg.elem_offset * 4;
-            P.hv = (char*)T.v + sg.elem_offset * 4;
-            P.bytes = (size_t)sg.count * 4;
-            ZI_HIP(hipMemcpyAsync(P.dp, P.hp, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
-            ZI_HIP(hipMemcpyAsync(P.dm, P.hm, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
-            ZI_HIP(hipMemcpyAsync(P.dv, P.hv, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
-            e->stats.bytes_h2d += 3 * P.bytes;
-            e->stats.n_copies += 3;
-        }
-        ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
-
-        ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
-        if (!e->skip_kernel) {
-            np = 0;
-            for (size_t j = s_begin; j < si; ++j, ++np) {
-                const Segment& sg = segs[j];
-                const zi_tensor& T = t[sg.tensor];
-                ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv,
-                                 (const uint16_t*)T.g + sg.elem_offset,
-                                 T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr, sg.count));
+            char* user_arr[3] = {(char*)T.p, (char*)T.m, (char*)T.v};
+            for (int w = 0; w < 3; ++w) {
+                char* up = user_arr[w] + sg.elem_offset * 4;
+                char* rp = (char*)(e->hslot_array(h, w) + slot_off(sg));
+                const size_t total = (size_t)sg.count * 4;
+                for (size_t o = 0; o < total; o += kCopyPieceBytes) {
+                    const size_t nb = total - o < kCopyPieceBytes ? total - o : kCopyPieceBytes;
+                    if (inbound) out.push_back({rp + o, up + o, nb});
+                    else         out.push_back({up + o, rp + o, nb});
+                }
             }
-            ZI_HIP(issue.flush());
-            e->stats.n_kernels += issue.launches;
         }
-        ZI_HIP(hipEventRecord(e->ev_k[slot], e->s_k));
+    };
 
-        ZI_HIP(hipStreamWaitEvent(e->s_d2h, e->ev_k[slot], 0));
-        for (int q = 0; q < np; ++q) {
-            const Placed& P = placed[q];
-            ZI_HIP(hipMemcpyAsync(P.hp, P.dp, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
-            ZI_HIP(hipMemcpyAsync(P.hm, P.dm, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
-            ZI_HIP(hipMemcpyAsync(P.hv, P.dv, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
-            e->stats.bytes_d2h += 3 * P.bytes;
-            e->stats.n_copies += 3;
-        }
-        ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
-        ++e->stats.n_slot_uses;
+    // Progress shared by the three actors of the ring path (gather thread, this thread, scatter thread).
+    struct {
+        std::mutex mu;
+        std::condition_variable cv;
+        int64_t gathered = 0, issued = 0, scattered = 0;
+        bool abort = false;
+        char scatter_err[160] = "";
+    } sync;
+    uint64_t staged_bytes = 0;
+    std::thread gather_thread, scatter_thread;
+    if (pageable) {
+        gather_thread = std::thread([&] {
+            std::vector<CopyPool::Piece> pieces;
+            for (int64_t u = 0; u < n_uses; ++u) {
+                {
+                    std::unique_lock<std::mutex> lk(sync.mu);
+                    sync.cv.wait(lk, [&] { return sync.abort || sync.scattered >= u - n_h + 1; });
+                    if (sync.abort) return;
+                }
+                ring_pieces(u, (int)(u % n_h), true, pieces);
+                e->pool_in->run(pieces);
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    sync.gathered = u + 1;
+                }
+                sync.cv.notify_all();
+            }
+        });
+        scatter_thread = std::thread([&] {
+            (void)hipSetDevice(e->device);
+            std::vector<CopyPool::Piece> pieces;
+            for (int64_t u = 0; u < n_uses; ++u) {
+                {
+                    std::unique_lock<std::mutex> lk(sync.mu);
+                    sync.cv.wait(lk, [&] { return sync.abort || sync.issued > u; });
+                    if (sync.abort) return;
+                }
+                const int h = (int)(u % n_h);
+                hipError_t he = hipEventSynchronize(e->ev_back[h]);
+                if (he != hipSuccess) {
+                    (void)hipGetLastError();
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    snprintf(sync.scatter_err, sizeof sync.scatter_err, "hipEventSynchronize: %s",
+                             hipGetErrorString(he));
+                    sync.abort = true;
+                    sync.cv.notify_all();
+                    return;
+                }
+                ring_pieces(u, h, false, pieces);
+                e->pool_out->run(pieces);
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    sync.scattered = u + 1;
+                }
+                sync.cv.notify_all();
+            }
+        });
     }
 
-    // Host arrays are valid on return; later work on the caller's stream sees the finished p_lp.
-    ZI_HIP(hipStreamSynchronize(e->s_d2h));
-    ZI_HIP(hipEventRecord(e->ev_out, e->s_k));
-    ZI_HIP(hipStreamWaitEvent(user, e->ev_out, 0));
-    ZI_HIP(hipStreamSynchronize(e->s_k));
+    const auto t0 = std::chrono::steady_clock::now();
+
+    auto pipeline = [&]() -> zi_status {
+        for (int64_t use = 0; use < n_uses; ++use) {
+            const int slot = (int)(use % e->n_slots);
+            const int h = pageable ? (int)(use % n_h) : 0;
+            if (pageable) {
+                std::unique_lock<std::mutex> lk(sync.mu);
+                sync.cv.wait(lk, [&] { return sync.abort || sync.gathered > use; });
+                if (sync.abort) return fail(ZI_ERR_HIP, "%s", sync.scatter_err);
+            }
+            // Slot reuse is ordered by the event of the device-to-host copies that last emptied it.
+            // Waiting for the OLDEST slot use keeps the host n_slots uses ahead of the copy engines.
+            if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_d2h[slot]));
+
+            struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes; };
+            Placed placed[zi::kMaxStepDesc];
+            StepIssuer issue(k, d_norm, (int)dt, l2, e->s_k);
+            int np = 0;
+            for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
+                const Segment& sg = segs[j];
+                const zi_tensor& T = t[sg.tensor];
+                const int64_t so = slot_off(sg);
+                Placed& P = placed[np];
+                P.dp = e->slot_array(slot, 0) + so;
+                P.dm = e->slot_array(slot, 1) + so;
+                P.dv = e->slot_array(slot, 2) + so;
+                if (pageable) {          // the link sees the pinned ring, not the caller's memory
+                    P.hp = (char*)(e->hslot_array(h, 0) + so);
+                    P.hm = (char*)(e->hslot_array(h, 1) + so);
+                    P.hv = (char*)(e->hslot_array(h, 2) + so);
+                } else {
+                    P.hp = (char*)T.p + sg.elem_offset * 4;
+                    P.hm = (char*)T.m + sg.elem_offset * 4;
+                    P.hv = (char*)T.v + sg.elem_offset * 4;
+                }
+                P.bytes = (size_t)sg.count * 4;
+                ZI_HIP(hipMemcpyAsync(P.dp, P.hp, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+                ZI_HIP(hipMemcpyAsync(P.dm, P.hm, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+                ZI_HIP(hipMemcpyAsync(P.dv, P.hv, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+                e->stats.bytes_h2d += 3 * P.bytes;
+                e->stats.n_copies += 3;
+                if (pageable) staged_bytes += 6 * P.bytes;
+            }
+            ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
+
+            ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
+            if (!e->skip_kernel) {
+                np = 0;
+                for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
+                    const Segment& sg = segs[j];
+                    const zi_tensor& T = t[sg.tensor];
+                    ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv,
+                                     (const uint16_t*)T.g + sg.elem_offset,
+                                     T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr, sg.count));
+                }
+                ZI_HIP(issue.flush());
+                e->stats.n_kernels += issue.launches;
+            }
+            ZI_HIP(hipEventRecord(e->ev_k[slot], e->s_k));
+
+            ZI_HIP(hipStreamWaitEvent(e->s_d2h, e->ev_k[slot], 0));
+            for (int q = 0; q < np; ++q) {
+                const Placed& P = placed[q];
+                ZI_HIP(hipMemcpyAsync(P.hp, P.dp, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                ZI_HIP(hipMemcpyAsync(P.hm, P.dm, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                ZI_HIP(hipMemcpyAsync(P.hv, P.dv, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                e->stats.bytes_d2h += 3 * P.bytes;
+                e->stats.n_copies += 3;
+            }
+            ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
+            if (pageable) {
+                ZI_HIP(hipEventRecord(e->ev_back[h], e->s_d2h));
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    sync.issued = use + 1;
+                }
+                sync.cv.notify_all();
+            }
+            ++e->stats.n_slot_uses;
+        }
+        // Host arrays are valid on return; later work on the caller's stream sees the finished p_lp.
+        ZI_HIP(hipStreamSynchronize(e->s_d2h));
+        ZI_HIP(hipEventRecord(e->ev_out, e->s_k));
+        ZI_HIP(hipStreamWaitEvent(user, e->ev_out, 0));
+        ZI_HIP(hipStreamSynchronize(e->s_k));
+        return ZI_OK;
+    };
+
+    zi_status st = pipeline();
+    if (pageable) {
+        if (st != ZI_OK) {
+            std::lock_guard<std::mutex> lk(sync.mu);
+            sync.abort = true;
+        }
+        sync.cv.notify_all();
+        gather_thread.join();
+        scatter_thread.join();
+        if (st == ZI_OK && sync.abort) st = fail(ZI_ERR_HIP, "%s", sync.scatter_err);
+    }
+    e->stats.bytes_staged_host = staged_bytes;
     e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
-    return ZI_OK;
+    return st;
 }
 
 extern "C" zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, void* host_dst, size_t bytes,

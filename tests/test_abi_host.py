@@ -34,6 +34,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(zi.zi_tensor) == 48
     assert ctypes.sizeof(zi.zi_adamw_config) == 48
     assert ctypes.sizeof(zi.zi_chunk_segment) == 40
+    assert ctypes.sizeof(zi.zi_stream_stats) == 56
     assert zi.zi_norm_workspace_bytes(10 ** 10, 50) == 16384 * 16
 
 

@@ -201,6 +201,56 @@ def test_c2_streamed_8e9_from_pinned_host():
             a.free()
 
 
+def test_c2_full_8e9_in_ordinary_host_memory_through_the_pinned_ring():
+    """The full host-resident workload: 8e9 elements = 96 GB of fp32 state in ordinary host memory, staged
+    through a 6-slot pinned ring (1.1 GiB) by CPU threads, 477 chunks of 64 MiB per array."""
+    w = zi_synth.workload("c2")
+    n, dt, spec = w["numel"][0], w["lp_dtype"], w["spec"]
+    chunk = w["chunk_bytes"] // 4
+    progress(f"c2-ring: generating 3 x {4 * n / 1e9:.0f} GB of ordinary host memory")
+    hp, hm, hv = (np.empty(n, np.float32) for _ in range(3))
+    piece = 1 << 30
+    for lo in range(0, n, piece):
+        c = min(piece, n - lo)
+        spec.fill_p(hp[lo:lo + c], c, 0, lo)
+        spec.fill_m(hm[lo:lo + c], c, 0, lo)
+        spec.fill_v(hv[lo:lo + c], c, 0, lo)
+        if (lo // piece) % 2 == 1:
+            progress(f"c2-ring: host state {lo + c}/{n}")
+    g = torch.empty(n, dtype=torch.int16, device="cuda:0")
+    fill_device_lp(lambda b, c, f: spec.fill_g(b, c, 0, f), n, g)
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 7)
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 6)
+        progress("c2-ring: streaming")
+        st = zi.zi_adamw_step_streamed(eng, [(hp, hm, hv, g, lp, n)], dt, zi_cfg(w), None,
+                                       torch.cuda.current_stream())
+        assert st == zi.ZI_OK
+        stats = zi.zi_engine_last_stats(eng)
+        assert stats.n_slot_uses == 477 and stats.bytes_h2d == 12 * n == stats.bytes_d2h
+        assert stats.bytes_staged_host == 24 * n
+        progress(f"c2-ring: streamed in {stats.seconds:.2f} s = {12 * n / stats.seconds / 1e9:.1f} GB/s per direction")
+    finally:
+        zi.zi_engine_destroy(eng)
+    tail0 = (n // chunk) * chunk
+    ranges = sample_ranges(n, WIDTH, extra_points=(chunk, 2 * chunk, 6 * chunk, 7 * chunk, 1 << 32, tail0),
+                           count=8, seed=5)
+    worst = ""
+    for lo, hi in ranges:
+        exp = oracle_range(spec, dt, oracle_cfg(w), lo, hi)
+        got = (hp[lo:hi].copy(), hm[lo:hi].copy(), hv[lo:hi].copy(), to_np(lp[lo:hi]))
+        worst = compare_state(exp, got, dt, f"c2-ring [{lo},{hi}) ")
+    stage = torch.empty(1 << 28, dtype=torch.float32, pin_memory=True)
+    for lo in range(0, n, 1 << 28):
+        c = min(1 << 28, n - lo)
+        stage.numpy()[:c] = hp[lo:lo + c]
+        want = stage[:c].to("cuda:0").to(torch.bfloat16).view(torch.int16)
+        assert torch.equal(want, lp[lo:lo + c]), f"copy/cast mismatch in [{lo},{lo + c})"
+    progress(f"c2-ring: {len(ranges)} ranges verified, copy consistent everywhere; last: {worst}")
+
+
 def test_c4_ragged_transformer_layers_streamed_with_clip():
     w = zi_synth.workload("c4")
     numel, dt, spec = w["numel"], w["lp_dtype"], w["spec"]

@@ -133,6 +133,53 @@ def test_step_allocates_nothing_and_rejects_pageable_state(engine):
     assert e.value.status == zi.ZI_ERR_INVALID_ARG and "pinned" in e.value.message
 
 
+@pytest.mark.parametrize("hslots,threads", [(2, 1), (4, 3), (7, 6)])
+def test_pageable_state_through_the_pinned_ring(hslots, threads):
+    """State in ordinary host memory, staged through a small pinned ring by CPU threads: same bits as the
+    resident step, for a flat tensor with a tail chunk and for a ragged list with packing."""
+    w = zi_synth.workload("c4")
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, threads)
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, hslots)
+        h = 128
+        lists = [[9 * 16384 + 1234], [n for _ in range(2) for (_, n) in zi_synth.transformer_layer_shapes(h)]]
+        for numel in lists:
+            spec = zi_synth.StateSpec(4321 + len(numel), zi.ZI_BF16, g_std=2e-3)
+            host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(numel)]
+            plain = [tuple(a.copy() for a in t[:3]) for t in host]           # ordinary numpy memory
+            dg = [to_dev(t[3]) for t in host]
+            dlp = [torch.zeros(t[3].size, dtype=torch.int16, device="cuda:0") for t in host]
+            nb = NormBuffers()
+            zi.zi_grad_norm([(None, None, None, g, None, g.numel()) for g in dg], zi.ZI_BF16, 1.0, nb.out, nb.ws)
+            tl = [(pp, pm, pv, g, lp, g.numel()) for (pp, pm, pv), g, lp in zip(plain, dg, dlp)]
+            st = zi.zi_adamw_step_streamed(eng, tl, zi.ZI_BF16, zi_cfg(w), nb.out, torch.cuda.current_stream())
+            assert st == zi.ZI_OK
+            stats = zi.zi_engine_last_stats(eng)
+            assert stats.bytes_staged_host == 24 * sum(numel) and stats.bytes_h2d == 12 * sum(numel)
+            # reference: the resident step on the same values
+            for (p, m, v, g), (pp, pm, pv), lp in zip(host, plain, dlp):
+                dp, dm, dv, dgg = (to_dev(a) for a in (p, m, v, g))
+                rlp = torch.zeros(p.size, dtype=torch.int16, device="cuda:0")
+                zi.zi_adamw_step([(dp, dm, dv, dgg, rlp, p.size)], zi.ZI_BF16, zi_cfg(w), nb.out)
+                torch.cuda.synchronize()
+                assert np.array_equal(pp.view(np.uint32), to_np(dp).view(np.uint32))
+                assert np.array_equal(pm.view(np.uint32), to_np(dm).view(np.uint32))
+                assert np.array_equal(pv.view(np.uint32), to_np(dv).view(np.uint32))
+                assert torch.equal(lp, rlp)
+        # turning the ring off again makes pageable state an error
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 0)
+        with pytest.raises(zi.ZiError):
+            zi.zi_adamw_step_streamed(eng, tl, zi.ZI_BF16, zi_cfg(w), nb.out)
+        for bad in (1, 17, -1):
+            with pytest.raises(zi.ZiError):
+                zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, bad)
+        with pytest.raises(zi.ZiError):
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 0)
+    finally:
+        zi.zi_engine_destroy(eng)
+
+
 def test_copy_only_option_and_link_probe(engine):
     n = 8 * 16384
     w = zi_synth.workload("c2")
