@@ -82,7 +82,8 @@ typedef enum {
     ZI_ERR_UNSUPPORTED = -2,
     ZI_ERR_ALIGNMENT = -3,
     ZI_ERR_HIP = -4,
-    ZI_ERR_NOMEM = -5
+    ZI_ERR_NOMEM = -5,
+    ZI_ERR_IO = -6
 } zi_status;
 
 typedef enum { ZI_BF16 = 0, ZI_FP16 = 1 } zi_lp_dtype;
@@ -162,7 +163,7 @@ zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, c
  * compute, device-to-host; all at default priority) and the events that order
  * slot reuse (Section 6.3: a small pool of reused buffers serves the whole
  * state).  Created once; step calls allocate nothing.
- * chunk_bytes_per_array: positive multiple of 256 (64 MiB is the usual value).
+ * chunk_bytes_per_array: positive multiple of 4096 (64 MiB is the usual value).
  * n_slots: 2..8.  device: HIP device ordinal.
  */
 typedef struct zi_engine zi_engine;
@@ -187,6 +188,48 @@ zi_status zi_engine_destroy(zi_engine* e);   /* NULL is accepted */
  */
 zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                                  const zi_adamw_config* cfg, const zi_norm_result* d_norm, void* hip_stream);
+
+/*
+ * The same step with p, m, v in FILES (Section 5.2.2: with NVMe offload the state is brought to
+ * faster memory and back in chunks, one chunk at a time; Section 6.3: bulk reads and writes issued
+ * in parallel, into and out of reused pinned buffers, no further copies).  Each chunk is read by
+ * the engine's CPU threads straight into a slot of the pinned ring (parallel pread), moved to HBM,
+ * updated, moved back and written out (parallel pwrite); reads, host-link copies, the kernel and
+ * writes of different chunks overlap.  Needs ZI_OPT_HOST_RING_SLOTS.
+ * fd_*: descriptors open O_RDWR; the caller keeps and closes them.  off_*: byte offset of the
+ * array inside its file (multiple of 4).  Descriptors opened with O_DIRECT are supported and
+ * recommended for NVMe: then every offset must be a multiple of 4096, no two arrays may share a
+ * 4096-byte block of a file, g must be 8-byte aligned, and transfers are rounded up to whole
+ * blocks (a file whose last region is not a multiple of 4096 bytes grows to the block boundary).
+ * Direct I/O passes through a small per-thread aligned buffer in ordinary memory, because memory
+ * from the HIP page-locked allocator cannot itself be the target of direct I/O; buffered
+ * descriptors read and write the pinned ring in place.
+ * g, p_lp: device memory, as in zi_adamw_step_streamed.  Blocking; data is written with pwrite,
+ * not synced (call fsync/fdatasync if durability is needed).  Results are bit-identical to
+ * zi_adamw_step on the same values.  A bad descriptor is ZI_ERR_INVALID_ARG; a failed or short read
+ * or write is ZI_ERR_IO with the errno text in zi_last_error(), and part of the state may then
+ * already have been updated.
+ */
+typedef struct {
+    int32_t fd_p, fd_m, fd_v;
+    int32_t reserved;
+    int64_t off_p, off_m, off_v;
+    const void* g;
+    void* p_lp;
+    int64_t numel;
+} zi_file_tensor;
+
+zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                              const zi_adamw_config* cfg, const zi_norm_result* d_norm, void* hip_stream);
+
+/*
+ * Storage probe: with the engine's thread pools and pinned ring, read `bytes` from fd_read
+ * (from offset 0) and, at the same time, write `bytes` to fd_write (from offset 0); either
+ * descriptor may be -1 to measure one direction alone.  bytes: positive multiple of 4096.
+ * Reports the elapsed seconds: the file-tier bandwidth the streamed step is bounded by.
+ */
+zi_status zi_engine_file_probe(zi_engine* e, int32_t fd_read, int32_t fd_write, size_t bytes,
+                               double* seconds_out);
 
 /* Figures of the engine's last streamed step (host memory, filled by the call). */
 typedef struct {

@@ -19,6 +19,7 @@ ZI_ERR_UNSUPPORTED = -2
 ZI_ERR_ALIGNMENT = -3
 ZI_ERR_HIP = -4
 ZI_ERR_NOMEM = -5
+ZI_ERR_IO = -6
 
 ZI_BF16 = 0
 ZI_FP16 = 1
@@ -31,7 +32,7 @@ ZI_OPT_HOST_COPY_THREADS = 2
 EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
-    "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
+    "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
 ]
 
 
@@ -56,6 +57,13 @@ class zi_norm_result(ctypes.Structure):
 class zi_tensor(ctypes.Structure):
     _fields_ = [("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("g", ctypes.c_void_p),
                 ("p_lp", ctypes.c_void_p), ("numel", ctypes.c_int64)]
+
+
+class zi_file_tensor(ctypes.Structure):
+    _fields_ = [("fd_p", ctypes.c_int32), ("fd_m", ctypes.c_int32), ("fd_v", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("off_p", ctypes.c_int64), ("off_m", ctypes.c_int64),
+                ("off_v", ctypes.c_int64), ("g", ctypes.c_void_p), ("p_lp", ctypes.c_void_p),
+                ("numel", ctypes.c_int64)]
 
 
 class zi_stream_stats(ctypes.Structure):
@@ -98,6 +106,11 @@ def lib() -> ctypes.CDLL:
         L.zi_adamw_step_streamed.restype = ctypes.c_int
         L.zi_adamw_step_streamed.argtypes = [vp, ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
                                              ctypes.POINTER(zi_adamw_config), vp, vp]
+        L.zi_adamw_step_files.restype = ctypes.c_int
+        L.zi_adamw_step_files.argtypes = [vp, ctypes.POINTER(zi_file_tensor), i32, ctypes.c_int,
+                                          ctypes.POINTER(zi_adamw_config), vp, vp]
+        L.zi_engine_file_probe.restype = ctypes.c_int
+        L.zi_engine_file_probe.argtypes = [vp, i32, i32, sz, ctypes.POINTER(ctypes.c_double)]
         L.zi_engine_last_stats.restype = ctypes.c_int
         L.zi_engine_last_stats.argtypes = [vp, ctypes.POINTER(zi_stream_stats)]
         L.zi_engine_set_option.restype = ctypes.c_int
@@ -213,6 +226,29 @@ def zi_adamw_step_streamed(engine, tensors, dt: int, cfg: zi_adamw_config, d_nor
     return _check(lib().zi_adamw_step_streamed(engine, arr, n, int(dt),
                                                ctypes.byref(cfg) if cfg is not None else None,
                                                _addr(d_norm), _stream(stream)))
+
+
+def make_file_tensors(items):
+    """ctypes array of zi_file_tensor from (fd_p, fd_m, fd_v, off_p, off_m, off_v, g, p_lp, numel) tuples."""
+    items = list(items)
+    arr = (zi_file_tensor * max(len(items), 1))()
+    for i, (fp, fm, fv, op, om, ov, g, p_lp, n) in enumerate(items):
+        arr[i] = zi_file_tensor(int(fp), int(fm), int(fv), 0, int(op), int(om), int(ov), _addr(g), _addr(p_lp),
+                                int(n))
+    return arr, len(items)
+
+
+def zi_adamw_step_files(engine, tensors, dt: int, cfg: zi_adamw_config, d_norm=None, stream=None) -> int:
+    arr, n = tensors if (isinstance(tensors, tuple) and len(tensors) == 2 and isinstance(tensors[0], ctypes.Array)) \
+        else make_file_tensors(tensors)
+    return _check(lib().zi_adamw_step_files(engine, arr, n, int(dt), ctypes.byref(cfg) if cfg is not None else None,
+                                            _addr(d_norm), _stream(stream)))
+
+
+def zi_engine_file_probe(engine, fd_read: int, fd_write: int, nbytes: int) -> float:
+    sec = ctypes.c_double()
+    _check(lib().zi_engine_file_probe(engine, int(fd_read), int(fd_write), int(nbytes), ctypes.byref(sec)))
+    return sec.value
 
 
 def zi_engine_last_stats(engine) -> zi_stream_stats:

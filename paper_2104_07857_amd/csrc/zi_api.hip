@@ -2,7 +2,11 @@
 // pinned-host <-> HBM streaming engine.  See include/zi.h for the contract of every call.
 #include <hip/hip_runtime.h>
 
+#include <fcntl.h>
+#include <unistd.h>
+
 #include <atomic>
+#include <cerrno>
 #include <chrono>
 #include <condition_variable>
 #include <mutex>
@@ -291,7 +295,7 @@ extern "C" zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_
 
 namespace {
 
-constexpr int64_t kPackAlign = 64;   // packed segments start on 256-byte boundaries of the slot arrays
+constexpr int64_t kPackAlign = 1024; // packed segments start on 4096-byte boundaries of the slot arrays (direct file I/O)
 constexpr int64_t kPhasePad = 8;     // room for up to 7 lead-in elements that keep 16-byte phases equal
 
 struct Segment {
@@ -370,11 +374,27 @@ extern "C" zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int
 
 namespace {
 
+constexpr size_t kCopyPieceBytes = 4u << 20;
+
 // A few threads that copy a list of (dst, src, bytes) pieces between ordinary host memory and the
 // pinned ring.  run() blocks until the whole list is copied; the calling thread takes part.
 class CopyPool {
 public:
-    struct Piece { char* dst; const char* src; size_t bytes; };
+    // op 0: memcpy(mem <- other).  op 1: pread(fd, mem, bytes, file_off), at least `need` bytes must
+    // arrive (a read rounded up for direct I/O may end at the end of the file).  op 2: pwrite.
+    // `bounce`: the descriptor does direct I/O.  Memory from the HIP page-locked allocator cannot be
+    // the target of direct I/O on this driver stack (the kernel refuses to pin it again: EFAULT), so
+    // such a piece goes through a 4096-byte aligned per-thread buffer in ordinary memory.
+    struct Piece {
+        int op;
+        char* mem;
+        const char* other;
+        int fd;
+        int64_t file_off;
+        size_t bytes;
+        size_t need;
+        bool bounce;
+    };
 
     explicit CopyPool(int n_threads)
     {
@@ -389,11 +409,13 @@ public:
         cv_job_.notify_all();
         for (auto& w : workers_) w.join();
     }
-    void run(const std::vector<Piece>& pieces)
+    // Returns 0, or the errno of the first failed piece (EIO for a short transfer).
+    int run(const std::vector<Piece>& pieces)
     {
         {
             std::lock_guard<std::mutex> lk(mu_);
             pieces_ = &pieces;
+            error_.store(0);
             next_.store(0);
             pending_ = (int)workers_.size();
             ++generation_;
@@ -403,14 +425,51 @@ public:
         std::unique_lock<std::mutex> lk(mu_);
         cv_done_.wait(lk, [this] { return pending_ == 0; });
         pieces_ = nullptr;
+        return error_.load();
     }
 
 private:
     void drain()
     {
         const std::vector<Piece>& ps = *pieces_;
-        for (size_t i = next_.fetch_add(1); i < ps.size(); i = next_.fetch_add(1))
-            std::memcpy(ps[i].dst, ps[i].src, ps[i].bytes);
+        for (size_t i = next_.fetch_add(1); i < ps.size(); i = next_.fetch_add(1)) {
+            const Piece& p = ps[i];
+            if (p.op == 0) {
+                std::memcpy(p.mem, p.other, p.bytes);
+                continue;
+            }
+            char* io = p.mem;
+            if (p.bounce) {
+                static thread_local char* tl_bounce = nullptr;
+                if (!tl_bounce && posix_memalign((void**)&tl_bounce, 4096, kCopyPieceBytes) != 0) {
+                    tl_bounce = nullptr;
+                    int expected = 0;
+                    error_.compare_exchange_strong(expected, ENOMEM);
+                    continue;
+                }
+                io = tl_bounce;
+                if (p.op == 2) std::memcpy(io, p.mem, p.bytes);
+            }
+            size_t done = 0;
+            while (done < p.bytes) {
+                const ssize_t r = p.op == 1 ? pread(p.fd, io + done, p.bytes - done, p.file_off + (int64_t)done)
+                                            : pwrite(p.fd, io + done, p.bytes - done, p.file_off + (int64_t)done);
+                if (r < 0) {
+                    if (errno == EINTR) continue;
+                    int expected = 0;
+                    error_.compare_exchange_strong(expected, errno);
+                    break;
+                }
+                if (r == 0) break;      // end of file
+                done += (size_t)r;
+            }
+            if (done < (p.op == 1 ? p.need : p.bytes)) {
+                int expected = 0;
+                error_.compare_exchange_strong(expected, EIO);
+            } else if (p.bounce && p.op == 1) {
+                std::memcpy(p.mem, io, done);
+            }
+        }
     }
     void loop()
     {
@@ -435,13 +494,13 @@ private:
     std::condition_variable cv_job_, cv_done_;
     const std::vector<Piece>* pieces_ = nullptr;
     std::atomic<size_t> next_{0};
+    std::atomic<int> error_{0};
     uint64_t generation_ = 0;
     int pending_ = 0;
     bool stop_ = false;
 };
 
 constexpr int kMaxHostSlots = 16;
-constexpr size_t kCopyPieceBytes = 4u << 20;
 
 }  // namespace
 
@@ -530,8 +589,8 @@ extern "C" zi_status zi_engine_create(zi_engine** out, int32_t device, size_t ch
     if (!out) return fail(ZI_ERR_INVALID_ARG, "out is NULL");
     *out = nullptr;
     if (device < 0) return fail(ZI_ERR_INVALID_ARG, "device < 0");
-    if (chunk_bytes_per_array == 0 || chunk_bytes_per_array % 256)
-        return fail(ZI_ERR_INVALID_ARG, "chunk_bytes_per_array must be a positive multiple of 256");
+    if (chunk_bytes_per_array == 0 || chunk_bytes_per_array % 4096)
+        return fail(ZI_ERR_INVALID_ARG, "chunk_bytes_per_array must be a positive multiple of 4096");
     if (chunk_bytes_per_array > ((size_t)1 << 34))
         return fail(ZI_ERR_INVALID_ARG, "chunk_bytes_per_array above 16 GiB");
     if (n_slots < 2 || n_slots > 8) return fail(ZI_ERR_INVALID_ARG, "n_slots must be in 2..8");
@@ -547,7 +606,7 @@ extern "C" zi_status zi_engine_create(zi_engine** out, int32_t device, size_t ch
     e->chunk_bytes = chunk_bytes_per_array;
     e->chunk_elems = (int64_t)(chunk_bytes_per_array / 4);
     e->n_slots = n_slots;
-    e->array_bytes = chunk_bytes_per_array + 256;
+    e->array_bytes = chunk_bytes_per_array + 4096;   // room for lead-in elements and a rounded-up last block
 
 #define ZI_HIP_E(call)                                                                           \
     do {                                                                                         \
@@ -650,6 +709,277 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
     return fail(ZI_ERR_INVALID_ARG, "unknown engine option %d", option);
 }
 
+namespace {
+
+enum { kSrcPinned = 0, kSrcPageable = 1, kSrcFile = 2 };
+
+// Where the fp32 state of one tensor lives for the streamed step.
+struct StateSrc {
+    int kind;
+    char* ptr[3];        // p, m, v (memory kinds)
+    int fd[3];           // file kind
+    int64_t off[3];
+    bool direct[3];      // descriptor was opened with O_DIRECT
+    const void* g;       // device
+    void* p_lp;          // device, may be null
+    int64_t numel;
+};
+
+// The chunk pipeline.  `staged` = the state is not page-locked memory and travels through the
+// engine's pinned ring (CPU threads fill and empty the ring slots).
+zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool staged, zi_lp_dtype dt,
+                       const zi_adamw_config* cfg, const zi_norm_result* d_norm, hipStream_t user)
+{
+    const int32_t n_tensors = (int32_t)src.size();
+    std::vector<int64_t> numel((size_t)n_tensors);
+    for (int32_t i = 0; i < n_tensors; ++i) numel[(size_t)i] = src[(size_t)i].numel;
+    std::vector<Segment> segs;
+    int64_t n_uses = 0;
+    try {
+        plan_chunks(numel.data(), n_tensors, e->chunk_elems, segs, n_uses);
+    } catch (const std::bad_alloc&) {
+        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+    }
+
+    // Overflow flag first: a skipped step moves nothing (4 bytes decide about gigabytes of traffic).
+    if (d_norm) {
+        ZI_HIP(hipMemcpyAsync(e->h_norm, d_norm, sizeof(zi_norm_result), hipMemcpyDeviceToHost, user));
+        ZI_HIP(hipStreamSynchronize(user));
+        if (e->h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
+    }
+
+    // Everything already enqueued on the caller's stream (gradients, norm) happens before our work.
+    ZI_HIP(hipEventRecord(e->ev_in, user));
+    ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
+    ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
+
+    const zi::StepConsts k = make_consts(*cfg);
+    const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
+    const int n_h = e->n_hslots;
+
+    // First segment of every slot use.
+    std::vector<size_t> use_begin((size_t)n_uses + 1, segs.size());
+    for (size_t j = segs.size(); j-- > 0;) use_begin[(size_t)segs[j].slot_use] = j;
+    for (int64_t u = n_uses - 1; u >= 0; --u)
+        if (use_begin[(size_t)u] > use_begin[(size_t)u + 1]) use_begin[(size_t)u] = use_begin[(size_t)u + 1];
+
+    // Where a segment sits inside a slot (HBM slot and pinned-ring slot share one layout).
+    auto slot_off = [&](const Segment& sg) -> int64_t {
+        const uint16_t* g = (const uint16_t*)src[(size_t)sg.tensor].g + sg.elem_offset;
+        // Lead-in elements that give the staged fp32 arrays the alignment phase of the gradients.
+        return sg.slot_offset + (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 4);
+    };
+    // Transfer lists between the caller's state (ordinary memory or files) and ring slot h for one
+    // slot use.  Direct-I/O files move whole 4096-byte blocks: the rounded-up tail of a region is read
+    // and written back unchanged (the update only touches `count` elements of the slot).
+    auto ring_pieces = [&](int64_t use, int h, bool inbound, std::vector<CopyPool::Piece>& out) {
+        out.clear();
+        for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
+            const Segment& sg = segs[j];
+            const StateSrc& S = src[(size_t)sg.tensor];
+            for (int w = 0; w < 3; ++w) {
+                char* rp = (char*)(e->hslot_array(h, w) + slot_off(sg));
+                const size_t need = (size_t)sg.count * 4;
+                if (S.kind == kSrcFile) {
+                    const size_t total = S.direct[w] ? (need + 4095) / 4096 * 4096 : need;
+                    const int64_t fo = S.off[w] + sg.elem_offset * 4;
+                    for (size_t o = 0; o < total; o += kCopyPieceBytes) {
+                        const size_t nb = total - o < kCopyPieceBytes ? total - o : kCopyPieceBytes;
+                        const size_t nd = o >= need ? 0 : (need - o < nb ? need - o : nb);
+                        out.push_back({inbound ? 1 : 2, rp + o, nullptr, S.fd[w], fo + (int64_t)o, nb, nd, S.direct[w]});
+                    }
+                } else {
+                    char* up = S.ptr[w] + sg.elem_offset * 4;
+                    for (size_t o = 0; o < need; o += kCopyPieceBytes) {
+                        const size_t nb = need - o < kCopyPieceBytes ? need - o : kCopyPieceBytes;
+                        if (inbound) out.push_back({0, rp + o, up + o, -1, 0, nb, nb, false});
+                        else         out.push_back({0, up + o, rp + o, -1, 0, nb, nb, false});
+                    }
+                }
+            }
+        }
+    };
+
+    // Progress shared by the three actors of the ring path (gather thread, this thread, scatter thread).
+    struct {
+        std::mutex mu;
+        std::condition_variable cv;
+        int64_t gathered = 0, issued = 0, scattered = 0;
+        bool abort = false;
+        bool io_error = false;
+        char scatter_err[160] = "";
+    } sync;
+    uint64_t staged_bytes = 0;
+    std::thread gather_thread, scatter_thread;
+    if (staged) {
+        gather_thread = std::thread([&] {
+            std::vector<CopyPool::Piece> pieces;
+            for (int64_t u = 0; u < n_uses; ++u) {
+                {
+                    std::unique_lock<std::mutex> lk(sync.mu);
+                    sync.cv.wait(lk, [&] { return sync.abort || sync.scattered >= u - n_h + 1; });
+                    if (sync.abort) return;
+                }
+                ring_pieces(u, (int)(u % n_h), true, pieces);
+                const int err = e->pool_in->run(pieces);
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    if (err) {
+                        snprintf(sync.scatter_err, sizeof sync.scatter_err, "reading state: %s", strerror(err));
+                        sync.abort = sync.io_error = true;
+                    } else {
+                        sync.gathered = u + 1;
+                    }
+                }
+                sync.cv.notify_all();
+                if (err) return;
+            }
+        });
+        scatter_thread = std::thread([&] {
+            (void)hipSetDevice(e->device);
+            std::vector<CopyPool::Piece> pieces;
+            for (int64_t u = 0; u < n_uses; ++u) {
+                {
+                    std::unique_lock<std::mutex> lk(sync.mu);
+                    sync.cv.wait(lk, [&] { return sync.abort || sync.issued > u; });
+                    if (sync.abort) return;
+                }
+                const int h = (int)(u % n_h);
+                hipError_t he = hipEventSynchronize(e->ev_back[h]);
+                if (he != hipSuccess) {
+                    (void)hipGetLastError();
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    snprintf(sync.scatter_err, sizeof sync.scatter_err, "hipEventSynchronize: %s",
+                             hipGetErrorString(he));
+                    sync.abort = true;
+                    sync.cv.notify_all();
+                    return;
+                }
+                ring_pieces(u, h, false, pieces);
+                const int err = e->pool_out->run(pieces);
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    if (err) {
+                        snprintf(sync.scatter_err, sizeof sync.scatter_err, "writing state: %s", strerror(err));
+                        sync.abort = sync.io_error = true;
+                    } else {
+                        sync.scattered = u + 1;
+                    }
+                }
+                sync.cv.notify_all();
+                if (err) return;
+            }
+        });
+    }
+
+    const auto t0 = std::chrono::steady_clock::now();
+
+    auto pipeline = [&]() -> zi_status {
+        for (int64_t use = 0; use < n_uses; ++use) {
+            const int slot = (int)(use % e->n_slots);
+            const int h = staged ? (int)(use % n_h) : 0;
+            if (staged) {
+                std::unique_lock<std::mutex> lk(sync.mu);
+                sync.cv.wait(lk, [&] { return sync.abort || sync.gathered > use; });
+                if (sync.abort) return fail(sync.io_error ? ZI_ERR_IO : ZI_ERR_HIP, "%s", sync.scatter_err);
+            }
+            // Slot reuse is ordered by the event of the device-to-host copies that last emptied it.
+            // Waiting for the OLDEST slot use keeps the host n_slots uses ahead of the copy engines.
+            if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_d2h[slot]));
+
+            struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes; };
+            Placed placed[zi::kMaxStepDesc];
+            StepIssuer issue(k, d_norm, (int)dt, l2, e->s_k);
+            int np = 0;
+            for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
+                const Segment& sg = segs[j];
+                const StateSrc& T = src[(size_t)sg.tensor];
+                const int64_t so = slot_off(sg);
+                Placed& P = placed[np];
+                P.dp = e->slot_array(slot, 0) + so;
+                P.dm = e->slot_array(slot, 1) + so;
+                P.dv = e->slot_array(slot, 2) + so;
+                if (staged) {          // the link sees the pinned ring, not the caller's memory
+                    P.hp = (char*)(e->hslot_array(h, 0) + so);
+                    P.hm = (char*)(e->hslot_array(h, 1) + so);
+                    P.hv = (char*)(e->hslot_array(h, 2) + so);
+                } else {
+                    P.hp = T.ptr[0] + sg.elem_offset * 4;
+                    P.hm = T.ptr[1] + sg.elem_offset * 4;
+                    P.hv = T.ptr[2] + sg.elem_offset * 4;
+                }
+                P.bytes = (size_t)sg.count * 4;
+                ZI_HIP(hipMemcpyAsync(P.dp, P.hp, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+                ZI_HIP(hipMemcpyAsync(P.dm, P.hm, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+                ZI_HIP(hipMemcpyAsync(P.dv, P.hv, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
+                e->stats.bytes_h2d += 3 * P.bytes;
+                e->stats.n_copies += 3;
+                if (staged) staged_bytes += 6 * P.bytes;
+            }
+            ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
+
+            ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
+            if (!e->skip_kernel) {
+                np = 0;
+                for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
+                    const Segment& sg = segs[j];
+                    const StateSrc& T = src[(size_t)sg.tensor];
+                    ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv,
+                                     (const uint16_t*)T.g + sg.elem_offset,
+                                     T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr, sg.count));
+                }
+                ZI_HIP(issue.flush());
+                e->stats.n_kernels += issue.launches;
+            }
+            ZI_HIP(hipEventRecord(e->ev_k[slot], e->s_k));
+
+            ZI_HIP(hipStreamWaitEvent(e->s_d2h, e->ev_k[slot], 0));
+            for (int q = 0; q < np; ++q) {
+                const Placed& P = placed[q];
+                ZI_HIP(hipMemcpyAsync(P.hp, P.dp, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                ZI_HIP(hipMemcpyAsync(P.hm, P.dm, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                ZI_HIP(hipMemcpyAsync(P.hv, P.dv, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                e->stats.bytes_d2h += 3 * P.bytes;
+                e->stats.n_copies += 3;
+            }
+            ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
+            if (staged) {
+                ZI_HIP(hipEventRecord(e->ev_back[h], e->s_d2h));
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    sync.issued = use + 1;
+                }
+                sync.cv.notify_all();
+            }
+            ++e->stats.n_slot_uses;
+        }
+        // Host arrays are valid on return; later work on the caller's stream sees the finished p_lp.
+        ZI_HIP(hipStreamSynchronize(e->s_d2h));
+        ZI_HIP(hipEventRecord(e->ev_out, e->s_k));
+        ZI_HIP(hipStreamWaitEvent(user, e->ev_out, 0));
+        ZI_HIP(hipStreamSynchronize(e->s_k));
+        return ZI_OK;
+    };
+
+    zi_status st = pipeline();
+    if (staged) {
+        if (st != ZI_OK) {
+            std::lock_guard<std::mutex> lk(sync.mu);
+            sync.abort = true;
+        }
+        sync.cv.notify_all();
+        gather_thread.join();
+        scatter_thread.join();
+        if (st == ZI_OK && sync.abort) st = fail(sync.io_error ? ZI_ERR_IO : ZI_ERR_HIP, "%s", sync.scatter_err);
+    }
+    e->stats.bytes_staged_host = staged_bytes;
+    e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return st;
+}
+
+
+}  // namespace
+
 extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                                             const zi_adamw_config* cfg, const zi_norm_result* d_norm,
                                             void* hip_stream)
@@ -687,226 +1017,100 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
         }
     }
 
-    std::vector<int64_t> numel((size_t)n_tensors);
-    for (int32_t i = 0; i < n_tensors; ++i) numel[(size_t)i] = t[i].numel;
-    std::vector<Segment> segs;
-    int64_t n_uses = 0;
-    try {
-        plan_chunks(numel.data(), n_tensors, e->chunk_elems, segs, n_uses);
-    } catch (const std::bad_alloc&) {
-        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+    std::vector<StateSrc> src((size_t)n_tensors);
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        StateSrc& S = src[(size_t)i];
+        S.kind = pageable ? kSrcPageable : kSrcPinned;
+        S.ptr[0] = (char*)t[i].p; S.ptr[1] = (char*)t[i].m; S.ptr[2] = (char*)t[i].v;
+        S.fd[0] = S.fd[1] = S.fd[2] = -1;
+        S.off[0] = S.off[1] = S.off[2] = 0;
+        S.direct[0] = S.direct[1] = S.direct[2] = false;
+        S.g = t[i].g; S.p_lp = t[i].p_lp; S.numel = t[i].numel;
     }
+    return run_streamed(e, src, pageable, dt, cfg, d_norm, user);
+}
 
-    // Overflow flag first: a skipped step moves nothing (4 bytes decide about gigabytes of traffic).
-    if (d_norm) {
-        ZI_HIP(hipMemcpyAsync(e->h_norm, d_norm, sizeof(zi_norm_result), hipMemcpyDeviceToHost, user));
-        ZI_HIP(hipStreamSynchronize(user));
-        if (e->h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
-    }
+extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                                         const zi_adamw_config* cfg, const zi_norm_result* d_norm,
+                                         void* hip_stream)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (zi_status st = check_dtype((int)dt)) return st;
+    if (zi_status st = check_config(cfg)) return st;
+    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
+    if (e->n_hslots == 0)
+        return fail(ZI_ERR_INVALID_ARG, "file-resident state needs a pinned ring (ZI_OPT_HOST_RING_SLOTS)");
 
-    // Everything already enqueued on the caller's stream (gradients, norm) happens before our work.
-    ZI_HIP(hipEventRecord(e->ev_in, user));
-    ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
-    ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
-
-    const zi::StepConsts k = make_consts(*cfg);
-    const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
-    const int n_h = e->n_hslots;
-
-    // First segment of every slot use.
-    std::vector<size_t> use_begin((size_t)n_uses + 1, segs.size());
-    for (size_t j = segs.size(); j-- > 0;) use_begin[(size_t)segs[j].slot_use] = j;
-    for (int64_t u = n_uses - 1; u >= 0; --u)
-        if (use_begin[(size_t)u] > use_begin[(size_t)u + 1]) use_begin[(size_t)u] = use_begin[(size_t)u + 1];
-
-    // Where a segment sits inside a slot (HBM slot and pinned-ring slot share one layout).
-    auto slot_off = [&](const Segment& sg) -> int64_t {
-        const uint16_t* g = (const uint16_t*)t[sg.tensor].g + sg.elem_offset;
-        // Lead-in elements that give the staged fp32 arrays the alignment phase of the gradients.
-        return sg.slot_offset + (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 4);
-    };
-    // Copy lists between the caller's ordinary memory and ring slot h for one slot use.
-    auto ring_pieces = [&](int64_t use, int h, bool inbound, std::vector<CopyPool::Piece>& out) {
-        out.clear();
-        for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
-            const Segment& sg = segs[j];
-            const zi_tensor& T = t[sg.tensor];
-            char* user_arr[3] = {(char*)T.p, (char*)T.m, (char*)T.v};
-            for (int w = 0; w < 3; ++w) {
-                char* up = user_arr[w] + sg.elem_offset * 4;
-                char* rp = (char*)(e->hslot_array(h, w) + slot_off(sg));
-                const size_t total = (size_t)sg.count * 4;
-                for (size_t o = 0; o < total; o += kCopyPieceBytes) {
-                    const size_t nb = total - o < kCopyPieceBytes ? total - o : kCopyPieceBytes;
-                    if (inbound) out.push_back({rp + o, up + o, nb});
-                    else         out.push_back({up + o, rp + o, nb});
-                }
+    std::vector<StateSrc> src((size_t)n_tensors);
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        StateSrc& S = src[(size_t)i];
+        S.kind = kSrcFile;
+        S.ptr[0] = S.ptr[1] = S.ptr[2] = nullptr;
+        S.fd[0] = t[i].fd_p; S.fd[1] = t[i].fd_m; S.fd[2] = t[i].fd_v;
+        S.off[0] = t[i].off_p; S.off[1] = t[i].off_m; S.off[2] = t[i].off_v;
+        S.g = t[i].g; S.p_lp = t[i].p_lp; S.numel = t[i].numel;
+        if (S.numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+        if (S.numel == 0) continue;
+        if (!S.g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
+        if (!aligned(S.g, 2) || !aligned(S.p_lp, 2))
+            return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
+        for (int w = 0; w < 3; ++w) {
+            const int fl = S.fd[w] >= 0 ? fcntl(S.fd[w], F_GETFL) : -1;
+            if (fl < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: bad file descriptor", i);
+            if ((fl & O_ACCMODE) != O_RDWR)
+                return fail(ZI_ERR_INVALID_ARG, "tensor %d: descriptors must be open for reading and writing", i);
+            if (S.off[w] < 0 || S.off[w] % 4) return fail(ZI_ERR_ALIGNMENT, "tensor %d: offsets must be multiples of 4", i);
+            S.direct[w] = (fl & O_DIRECT) != 0;
+            if (S.direct[w]) {
+                if (S.off[w] % 4096)
+                    return fail(ZI_ERR_ALIGNMENT, "tensor %d: with O_DIRECT, offsets must be multiples of 4096", i);
+                if (!aligned(S.g, 8))
+                    return fail(ZI_ERR_ALIGNMENT, "tensor %d: with O_DIRECT, g must be 8-byte aligned", i);
             }
         }
-    };
-
-    // Progress shared by the three actors of the ring path (gather thread, this thread, scatter thread).
-    struct {
-        std::mutex mu;
-        std::condition_variable cv;
-        int64_t gathered = 0, issued = 0, scattered = 0;
-        bool abort = false;
-        char scatter_err[160] = "";
-    } sync;
-    uint64_t staged_bytes = 0;
-    std::thread gather_thread, scatter_thread;
-    if (pageable) {
-        gather_thread = std::thread([&] {
-            std::vector<CopyPool::Piece> pieces;
-            for (int64_t u = 0; u < n_uses; ++u) {
-                {
-                    std::unique_lock<std::mutex> lk(sync.mu);
-                    sync.cv.wait(lk, [&] { return sync.abort || sync.scattered >= u - n_h + 1; });
-                    if (sync.abort) return;
-                }
-                ring_pieces(u, (int)(u % n_h), true, pieces);
-                e->pool_in->run(pieces);
-                {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    sync.gathered = u + 1;
-                }
-                sync.cv.notify_all();
-            }
-        });
-        scatter_thread = std::thread([&] {
-            (void)hipSetDevice(e->device);
-            std::vector<CopyPool::Piece> pieces;
-            for (int64_t u = 0; u < n_uses; ++u) {
-                {
-                    std::unique_lock<std::mutex> lk(sync.mu);
-                    sync.cv.wait(lk, [&] { return sync.abort || sync.issued > u; });
-                    if (sync.abort) return;
-                }
-                const int h = (int)(u % n_h);
-                hipError_t he = hipEventSynchronize(e->ev_back[h]);
-                if (he != hipSuccess) {
-                    (void)hipGetLastError();
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    snprintf(sync.scatter_err, sizeof sync.scatter_err, "hipEventSynchronize: %s",
-                             hipGetErrorString(he));
-                    sync.abort = true;
-                    sync.cv.notify_all();
-                    return;
-                }
-                ring_pieces(u, h, false, pieces);
-                e->pool_out->run(pieces);
-                {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    sync.scattered = u + 1;
-                }
-                sync.cv.notify_all();
-            }
-        });
     }
+    ZI_HIP(hipSetDevice(e->device));
+    e->stats = zi_stream_stats{};
+    return run_streamed(e, src, true, dt, cfg, d_norm, (hipStream_t)hip_stream);
+}
 
+extern "C" zi_status zi_engine_file_probe(zi_engine* e, int32_t fd_read, int32_t fd_write, size_t bytes,
+                                          double* seconds_out)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (!seconds_out) return fail(ZI_ERR_INVALID_ARG, "seconds_out is NULL");
+    if (e->n_hslots == 0) return fail(ZI_ERR_INVALID_ARG, "the probe needs a pinned ring (ZI_OPT_HOST_RING_SLOTS)");
+    if (fd_read < 0 && fd_write < 0) return fail(ZI_ERR_INVALID_ARG, "no file descriptor given");
+    if (bytes == 0 || bytes % 4096) return fail(ZI_ERR_INVALID_ARG, "bytes must be a positive multiple of 4096");
+    if (e->n_hslots < 2) return fail(ZI_ERR_INVALID_ARG, "ring too small");
+    // Reads land in the first half of the ring, writes leave from the second half.
+    const size_t half = (size_t)(e->n_hslots / 2) * 3 * e->array_bytes / 4096 * 4096;
+    auto pieces_for = [&](int fd, int op, char* base, std::vector<CopyPool::Piece>& out) {
+        const int fl = fcntl(fd, F_GETFL);
+        const bool direct = fl >= 0 && (fl & O_DIRECT);
+        size_t ring_o = 0;
+        for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
+            const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
+            if (ring_o + nb > half) ring_o = 0;
+            out.push_back({op, base + ring_o, nullptr, fd, (int64_t)o, nb, nb, direct});
+            ring_o += nb;
+        }
+    };
+    std::vector<CopyPool::Piece> rd, wr;
+    if (fd_read >= 0) pieces_for(fd_read, 1, e->hring, rd);
+    if (fd_write >= 0) pieces_for(fd_write, 2, e->hring + half, wr);
+    int err_r = 0, err_w = 0;
     const auto t0 = std::chrono::steady_clock::now();
-
-    auto pipeline = [&]() -> zi_status {
-        for (int64_t use = 0; use < n_uses; ++use) {
-            const int slot = (int)(use % e->n_slots);
-            const int h = pageable ? (int)(use % n_h) : 0;
-            if (pageable) {
-                std::unique_lock<std::mutex> lk(sync.mu);
-                sync.cv.wait(lk, [&] { return sync.abort || sync.gathered > use; });
-                if (sync.abort) return fail(ZI_ERR_HIP, "%s", sync.scatter_err);
-            }
-            // Slot reuse is ordered by the event of the device-to-host copies that last emptied it.
-            // Waiting for the OLDEST slot use keeps the host n_slots uses ahead of the copy engines.
-            if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_d2h[slot]));
-
-            struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes; };
-            Placed placed[zi::kMaxStepDesc];
-            StepIssuer issue(k, d_norm, (int)dt, l2, e->s_k);
-            int np = 0;
-            for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
-                const Segment& sg = segs[j];
-                const zi_tensor& T = t[sg.tensor];
-                const int64_t so = slot_off(sg);
-                Placed& P = placed[np];
-                P.dp = e->slot_array(slot, 0) + so;
-                P.dm = e->slot_array(slot, 1) + so;
-                P.dv = e->slot_array(slot, 2) + so;
-                if (pageable) {          // the link sees the pinned ring, not the caller's memory
-                    P.hp = (char*)(e->hslot_array(h, 0) + so);
-                    P.hm = (char*)(e->hslot_array(h, 1) + so);
-                    P.hv = (char*)(e->hslot_array(h, 2) + so);
-                } else {
-                    P.hp = (char*)T.p + sg.elem_offset * 4;
-                    P.hm = (char*)T.m + sg.elem_offset * 4;
-                    P.hv = (char*)T.v + sg.elem_offset * 4;
-                }
-                P.bytes = (size_t)sg.count * 4;
-                ZI_HIP(hipMemcpyAsync(P.dp, P.hp, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
-                ZI_HIP(hipMemcpyAsync(P.dm, P.hm, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
-                ZI_HIP(hipMemcpyAsync(P.dv, P.hv, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
-                e->stats.bytes_h2d += 3 * P.bytes;
-                e->stats.n_copies += 3;
-                if (pageable) staged_bytes += 6 * P.bytes;
-            }
-            ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
-
-            ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
-            if (!e->skip_kernel) {
-                np = 0;
-                for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
-                    const Segment& sg = segs[j];
-                    const zi_tensor& T = t[sg.tensor];
-                    ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv,
-                                     (const uint16_t*)T.g + sg.elem_offset,
-                                     T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr, sg.count));
-                }
-                ZI_HIP(issue.flush());
-                e->stats.n_kernels += issue.launches;
-            }
-            ZI_HIP(hipEventRecord(e->ev_k[slot], e->s_k));
-
-            ZI_HIP(hipStreamWaitEvent(e->s_d2h, e->ev_k[slot], 0));
-            for (int q = 0; q < np; ++q) {
-                const Placed& P = placed[q];
-                ZI_HIP(hipMemcpyAsync(P.hp, P.dp, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
-                ZI_HIP(hipMemcpyAsync(P.hm, P.dm, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
-                ZI_HIP(hipMemcpyAsync(P.hv, P.dv, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
-                e->stats.bytes_d2h += 3 * P.bytes;
-                e->stats.n_copies += 3;
-            }
-            ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
-            if (pageable) {
-                ZI_HIP(hipEventRecord(e->ev_back[h], e->s_d2h));
-                {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    sync.issued = use + 1;
-                }
-                sync.cv.notify_all();
-            }
-            ++e->stats.n_slot_uses;
-        }
-        // Host arrays are valid on return; later work on the caller's stream sees the finished p_lp.
-        ZI_HIP(hipStreamSynchronize(e->s_d2h));
-        ZI_HIP(hipEventRecord(e->ev_out, e->s_k));
-        ZI_HIP(hipStreamWaitEvent(user, e->ev_out, 0));
-        ZI_HIP(hipStreamSynchronize(e->s_k));
-        return ZI_OK;
-    };
-
-    zi_status st = pipeline();
-    if (pageable) {
-        if (st != ZI_OK) {
-            std::lock_guard<std::mutex> lk(sync.mu);
-            sync.abort = true;
-        }
-        sync.cv.notify_all();
-        gather_thread.join();
-        scatter_thread.join();
-        if (st == ZI_OK && sync.abort) st = fail(ZI_ERR_HIP, "%s", sync.scatter_err);
-    }
-    e->stats.bytes_staged_host = staged_bytes;
-    e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
-    return st;
+    std::thread tw;
+    if (!wr.empty()) tw = std::thread([&] { err_w = e->pool_out->run(wr); });
+    if (!rd.empty()) err_r = e->pool_in->run(rd);
+    if (tw.joinable()) tw.join();
+    *seconds_out = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    if (err_r) return fail(ZI_ERR_IO, "reading: %s", strerror(err_r));
+    if (err_w) return fail(ZI_ERR_IO, "writing: %s", strerror(err_w));
+    return ZI_OK;
 }
 
 extern "C" zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, void* host_dst, size_t bytes,

@@ -20,7 +20,7 @@ def _declared_functions():
 
 def test_library_exports_every_declared_symbol():
     declared = _declared_functions()
-    assert len(declared) >= 14
+    assert len(declared) >= 16
     L = ctypes.CDLL(zi.LIB_PATH)
     for name in declared:
         assert hasattr(L, name), f"{name} declared in include/zi.h but not exported"
@@ -35,6 +35,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(zi.zi_adamw_config) == 48
     assert ctypes.sizeof(zi.zi_chunk_segment) == 40
     assert ctypes.sizeof(zi.zi_stream_stats) == 56
+    assert ctypes.sizeof(zi.zi_file_tensor) == 64
     assert zi.zi_norm_workspace_bytes(10 ** 10, 50) == 16384 * 16
 
 
@@ -114,7 +115,7 @@ def test_norm_rejects_bad_arguments():
 
 
 def test_engine_and_misc_argument_checks():
-    for args in ((0, 0, 3), (0, 100, 3), (0, 1 << 20, 1), (0, 1 << 20, 9), (-1, 1 << 20, 3)):
+    for args in ((0, 0, 3), (0, 100, 3), (0, 256, 3), (0, 1 << 20, 1), (0, 1 << 20, 9), (-1, 1 << 20, 3)):
         with pytest.raises(zi.ZiError) as e:
             zi.zi_engine_create(*args)
         assert e.value.status == zi.ZI_ERR_INVALID_ARG
@@ -126,6 +127,11 @@ def test_engine_and_misc_argument_checks():
     with pytest.raises(zi.ZiError) as e:
         zi.zi_adamw_step_streamed(None, [(p, m, v, g, lp)], zi.ZI_BF16, zi.make_config())
     assert e.value.status == zi.ZI_ERR_INVALID_ARG
+    with pytest.raises(zi.ZiError) as e:
+        zi.zi_adamw_step_files(None, [], zi.ZI_BF16, zi.make_config())
+    assert e.value.status == zi.ZI_ERR_INVALID_ARG
+    with pytest.raises(zi.ZiError):
+        zi.zi_engine_file_probe(None, -1, -1, 4096)
     with pytest.raises(zi.ZiError):
         zi.zi_engine_last_stats(None)
     with pytest.raises(zi.ZiError):
@@ -152,7 +158,7 @@ def _check_plan(numel, chunk):
         assert s.slot_use >= last_use, "segments come sorted by slot use"
         last_use = s.slot_use
         per_use.setdefault(s.slot_use, []).append(s)
-        assert s.slot_offset % 64 == 0
+        assert s.slot_offset % 1024 == 0
         assert s.slot_offset + s.count <= chunk + 0 or (s.slot_offset == 0 and s.count <= chunk)
     assert covered == list(numel), "every element travels exactly once"
     assert sorted(per_use) == list(range(uses)), "slot uses are numbered without gaps"
@@ -176,18 +182,18 @@ def test_chunk_plans_of_the_workloads():
 
 
 def test_chunk_plans_of_awkward_lists():
-    _check_plan([], 64)
-    _check_plan([0, 0], 64)
-    _check_plan([1], 64)
-    _check_plan([63, 64, 65, 1, 0, 200, 57, 56, 55], 64)
-    _check_plan([5] * 100, 128)                       # more small tensors than one launch takes
-    _check_plan([1000, 3, 1000, 3, 999, 17], 256)
+    _check_plan([], 1024)
+    _check_plan([0, 0], 1024)
+    _check_plan([1], 1024)
+    _check_plan([1023, 1024, 1025, 1, 0, 3000, 1017, 1016, 1015], 1024)
+    _check_plan([5] * 100, 8192)                      # more small tensors than one launch takes
+    _check_plan([10000, 3, 10000, 3, 9999, 17], 2048)
     rng = np.random.default_rng(0)
     for _ in range(50):
         k = int(rng.integers(1, 40))
-        numel = [int(x) for x in rng.integers(0, 5000, k)]
-        _check_plan(numel, int(rng.choice([64, 128, 1024, 4096])))
-    for bad in (0, 63, 100, -64):
+        numel = [int(x) for x in rng.integers(0, 50000, k)]
+        _check_plan(numel, int(rng.choice([1024, 2048, 8192, 16384])))
+    for bad in (0, 63, 100, -1024, 1536):
         with pytest.raises(zi.ZiError):
             zi.zi_plan_chunks([10], bad)
     with pytest.raises(zi.ZiError):

@@ -8,6 +8,8 @@ every bit in place.
 """
 import ctypes
 import math
+import os
+import tempfile
 
 import numpy as np
 import pytest
@@ -249,6 +251,69 @@ def test_c2_full_8e9_in_ordinary_host_memory_through_the_pinned_ring():
         want = stage[:c].to("cuda:0").to(torch.bfloat16).view(torch.int16)
         assert torch.equal(want, lp[lo:lo + c]), f"copy/cast mismatch in [{lo},{lo + c})"
     progress(f"c2-ring: {len(ranges)} ranges verified, copy consistent everywhere; last: {worst}")
+
+
+def test_file_tier_one_gibi_elements_direct_io():
+    """State in files on the box's disk (3 x 4 GiB, O_DIRECT), 64 MiB chunks through a 6-slot pinned ring:
+    sample ranges against the oracle, and the step's rate beside the storage probe's."""
+    w = zi_synth.workload("c2")
+    n, dt, spec = 1 << 30, w["lp_dtype"], w["spec"]
+    chunk = w["chunk_bytes"] // 4
+    eng = None
+    fds = []
+    with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
+        try:
+            paths = [os.path.join(tmp, k + ".bin") for k in "pmv"]
+            buf = np.empty(1 << 28, np.float32)
+            for path, fill in zip(paths, (spec.fill_p, spec.fill_m, spec.fill_v)):
+                with open(path, "wb") as f:
+                    for lo in range(0, n, buf.size):
+                        fill(buf, buf.size, 0, lo)
+                        f.write(buf.tobytes())
+                progress(f"file tier: wrote {path}")
+            os.sync()
+            fds = [os.open(p, os.O_RDWR | os.O_DIRECT) for p in paths]
+            g = torch.empty(n, dtype=torch.int16, device="cuda:0")
+            fill_device_lp(lambda b, c, f: spec.fill_g(b, c, 0, f), n, g)
+            lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+            eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 8)
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 6)
+            nbytes = 4 * n
+            rd = nbytes / zi.zi_engine_file_probe(eng, fds[0], -1, nbytes) / 1e9
+            scratch = os.open(os.path.join(tmp, "scratch.bin"), os.O_RDWR | os.O_CREAT | os.O_DIRECT, 0o600)
+            fds.append(scratch)
+            wr = nbytes / zi.zi_engine_file_probe(eng, -1, scratch, nbytes) / 1e9
+            both = nbytes / zi.zi_engine_file_probe(eng, fds[1], scratch, nbytes) / 1e9
+            progress(f"file tier: storage probe read {rd:.2f} GB/s, write {wr:.2f} GB/s, both at once {both:.2f} GB/s each")
+            st = zi.zi_adamw_step_files(eng, [(fds[0], fds[1], fds[2], 0, 0, 0, g, lp, n)], dt, zi_cfg(w), None,
+                                        torch.cuda.current_stream())
+            assert st == zi.ZI_OK
+            stats = zi.zi_engine_last_stats(eng)
+            assert stats.n_slot_uses == n // chunk and stats.bytes_h2d == 12 * n
+            rate = 12 * n / stats.seconds / 1e9
+            progress(f"file tier: step in {stats.seconds:.2f} s = {rate:.2f} GB/s read and {rate:.2f} GB/s written "
+                     f"({rate / both:.2f} of the two-way probe)")
+            for fd in fds:
+                os.close(fd)
+            fds = []
+            maps = [np.memmap(p, dtype=np.float32, mode="r") for p in paths]
+            ranges = sample_ranges(n, WIDTH, extra_points=(chunk, 5 * chunk, 6 * chunk), count=6, seed=7)
+            worst = ""
+            for lo, hi in ranges:
+                exp = oracle_range(spec, dt, oracle_cfg(w), lo, hi)
+                got = tuple(np.array(mm[lo:hi]) for mm in maps) + (to_np(lp[lo:hi]),)
+                worst = compare_state(exp, got, dt, f"file tier [{lo},{hi}) ")
+            for lo in range(0, n, 1 << 28):
+                want = torch.from_numpy(np.array(maps[0][lo:lo + (1 << 28)])).to("cuda:0").to(torch.bfloat16)
+                assert torch.equal(want.view(torch.int16), lp[lo:lo + (1 << 28)])
+            del maps
+            progress(f"file tier: {len(ranges)} ranges verified, copy consistent everywhere; last: {worst}")
+        finally:
+            for fd in fds:
+                os.close(fd)
+            if eng is not None:
+                zi.zi_engine_destroy(eng)
 
 
 def test_c4_ragged_transformer_layers_streamed_with_clip():

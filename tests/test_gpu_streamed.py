@@ -1,4 +1,7 @@
 """The streamed step (state in pinned host memory, chunked through HBM) against the oracle and the resident step."""
+import os
+import tempfile
+
 import numpy as np
 import pytest
 import torch
@@ -178,6 +181,117 @@ def test_pageable_state_through_the_pinned_ring(hslots, threads):
             zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 0)
     finally:
         zi.zi_engine_destroy(eng)
+
+
+def _write_state_files(tmp, host, direct):
+    """One file per array kind; tensor i of the list starts at a 4096-byte aligned offset."""
+    offs, pos = [], 0
+    for (p, m, v, g) in host:
+        offs.append(pos)
+        pos += (4 * p.size + 4095) // 4096 * 4096
+    paths = [os.path.join(tmp, k + ".bin") for k in "pmv"]
+    for w, path in enumerate(paths):
+        with open(path, "wb") as f:
+            for o, tensors in zip(offs, host):
+                f.seek(o)
+                f.write(tensors[w].tobytes())
+            f.truncate(max(pos, 4096))
+    flags = os.O_RDWR | (os.O_DIRECT if direct else 0)
+    return [os.open(p, flags) for p in paths], offs, paths
+
+
+@pytest.mark.parametrize("direct", [False, True])
+def test_state_in_files_through_the_pinned_ring(direct):
+    """fp32 state in files (buffered and O_DIRECT descriptors): parallel reads into the pinned ring, the
+    same device pipeline, parallel writes back.  Bit-identical to the resident step."""
+    w = zi_synth.workload("c4")
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    fds = []
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 4)
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 5)
+        h = 128
+        lists = [[9 * 16384 + 1236], [n for _ in range(2) for (_, n) in zi_synth.transformer_layer_shapes(h)]]
+        for numel in lists:
+            spec = zi_synth.StateSpec(777 + len(numel), zi.ZI_BF16, g_std=2e-3)
+            host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(numel)]
+            with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
+                fds, offs, paths = _write_state_files(tmp, host, direct)
+                dg = [to_dev(t[3]) for t in host]
+                dlp = [torch.zeros(t[3].size, dtype=torch.int16, device="cuda:0") for t in host]
+                nb = NormBuffers()
+                zi.zi_grad_norm([(None, None, None, g, None, g.numel()) for g in dg], zi.ZI_BF16, 1.0, nb.out, nb.ws)
+                tl = [(fds[0], fds[1], fds[2], o, o, o, g, lp, g.numel()) for o, g, lp in zip(offs, dg, dlp)]
+                st = zi.zi_adamw_step_files(eng, tl, zi.ZI_BF16, zi_cfg(w), nb.out, torch.cuda.current_stream())
+                assert st == zi.ZI_OK
+                stats = zi.zi_engine_last_stats(eng)
+                assert stats.bytes_h2d == 12 * sum(numel) == stats.bytes_d2h
+                for fd in fds:
+                    os.close(fd)
+                fds = []
+                back = [np.fromfile(p, dtype=np.float32) for p in paths]
+                for (p, m, v, g), o, lp in zip(host, offs, dlp):
+                    dp, dm, dv, dgg = (to_dev(a) for a in (p, m, v, g))
+                    rlp = torch.zeros(p.size, dtype=torch.int16, device="cuda:0")
+                    zi.zi_adamw_step([(dp, dm, dv, dgg, rlp, p.size)], zi.ZI_BF16, zi_cfg(w), nb.out)
+                    torch.cuda.synchronize()
+                    for arr, ref in zip(back, (dp, dm, dv)):
+                        got = arr[o // 4:o // 4 + p.size]
+                        assert np.array_equal(got.view(np.uint32), to_np(ref).view(np.uint32))
+                    assert torch.equal(lp, rlp)
+    finally:
+        for fd in fds:
+            os.close(fd)
+        zi.zi_engine_destroy(eng)
+
+
+def test_file_step_argument_and_io_errors():
+    n = 3 * 16384
+    g = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    cfg = zi.make_config(step=10)
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
+        path = os.path.join(tmp, "s.bin")
+        with open(path, "wb") as f:
+            f.write(np.zeros(3 * n, np.float32).tobytes())
+        fd = os.open(path, os.O_RDWR)
+        fdro = os.open(path, os.O_RDONLY)
+        fdd = os.open(path, os.O_RDWR | os.O_DIRECT)
+        try:
+            good = (fd, fd, fd, 0, 4 * n, 8 * n, g, lp, n)
+            with pytest.raises(zi.ZiError) as e:                     # no ring yet
+                zi.zi_adamw_step_files(eng, [good], zi.ZI_BF16, cfg)
+            assert e.value.status == zi.ZI_ERR_INVALID_ARG
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 4)
+            assert zi.zi_adamw_step_files(eng, [good], zi.ZI_BF16, cfg) == zi.ZI_OK
+            assert zi.zi_adamw_step_files(eng, [], zi.ZI_BF16, cfg) == zi.ZI_OK
+            for bad, status in (((-1, fd, fd, 0, 0, 0, g, lp, n), zi.ZI_ERR_INVALID_ARG),
+                                ((987654, fd, fd, 0, 0, 0, g, lp, n), zi.ZI_ERR_INVALID_ARG),
+                                ((fdro, fd, fd, 0, 4 * n, 8 * n, g, lp, n), zi.ZI_ERR_INVALID_ARG),
+                                ((fd, fd, fd, 2, 4 * n, 8 * n, g, lp, n), zi.ZI_ERR_ALIGNMENT),
+                                ((fdd, fd, fd, 512, 4 * n, 8 * n, g, lp, n), zi.ZI_ERR_ALIGNMENT),
+                                ((fdd, fd, fd, 0, 4 * n, 8 * n, g[1:], lp[1:], n - 1), zi.ZI_ERR_ALIGNMENT),
+                                ((fd, fd, fd, 0, 4 * n, 8 * n, None, lp, n), zi.ZI_ERR_INVALID_ARG),
+                                ((fd, fd, fd, 0, 4 * n, 8 * n, g, lp, -5), zi.ZI_ERR_INVALID_ARG)):
+                with pytest.raises(zi.ZiError) as e:
+                    zi.zi_adamw_step_files(eng, [bad], zi.ZI_BF16, cfg)
+                assert e.value.status == status, bad
+            # the v region lies beyond the end of the file: a short read is an I/O error, not a crash
+            with pytest.raises(zi.ZiError) as e:
+                zi.zi_adamw_step_files(eng, [(fd, fd, fd, 0, 4 * n, 16 * n, g, lp, n)], zi.ZI_BF16, cfg)
+            assert e.value.status == zi.ZI_ERR_IO and "reading" in e.value.message
+            # the engine is still usable afterwards
+            assert zi.zi_adamw_step_files(eng, [good], zi.ZI_BF16, cfg) == zi.ZI_OK
+            assert zi.zi_engine_file_probe(eng, fd, -1, 4096 * 8) > 0
+            with pytest.raises(zi.ZiError):
+                zi.zi_engine_file_probe(eng, -1, -1, 4096)
+            with pytest.raises(zi.ZiError):
+                zi.zi_engine_file_probe(eng, fd, -1, 1000)
+        finally:
+            for d in (fd, fdro, fdd):
+                os.close(d)
+            zi.zi_engine_destroy(eng)
 
 
 def test_copy_only_option_and_link_probe(engine):
