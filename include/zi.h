@@ -158,8 +158,9 @@ zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, c
                         const zi_norm_result* d_norm, void* hip_stream);
 
 /*
- * Streaming engine: owns n_slots staging slots in HBM (each 3 arrays of
- * chunk_bytes_per_array for p, m, v), three HIP streams (host-to-device,
+ * Streaming engine: owns n_slots staging slots in HBM (each 4 arrays of
+ * chunk_bytes_per_array: p, m, v, and one shared by staged gradients and a
+ * staged low-precision copy), three HIP streams (host-to-device,
  * compute, device-to-host; all at default priority) and the events that order
  * slot reuse (Section 6.3: a small pool of reused buffers serves the whole
  * state).  Created once; step calls allocate nothing.
@@ -188,6 +189,21 @@ zi_status zi_engine_destroy(zi_engine* e);   /* NULL is accepted */
  */
 zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                                  const zi_adamw_config* cfg, const zi_norm_result* d_norm, void* hip_stream);
+
+/*
+ * Gradients and the low-precision copy need not be on the device for the streamed step: if
+ * t[i].g (and / or t[i].p_lp) of zi_adamw_step_streamed is host memory (pinned, or ordinary with a
+ * pinned ring), each chunk of gradients travels to HBM with its chunk of state, and the chunk of
+ * the low-precision copy travels back with it (14 bytes per element each way instead of 12).
+ * This is the gradient-side offload of Section 6.2 (gradients moved to slow memory during the
+ * backward pass) seen from the optimizer step.  zi_grad_norm_streamed is the matching reduction:
+ * as zi_grad_norm, but gradients in host memory are staged through the engine's slots chunk by
+ * chunk (2 bytes per element over the link), overlapped with the reduction kernels; device-resident
+ * gradients in the same list are reduced in place.  BLOCKING: returns when the result is in d_out.
+ */
+zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                                float loss_scale, zi_norm_result* d_out, void* d_workspace,
+                                size_t workspace_bytes, void* hip_stream);
 
 /*
  * The same step with p, m, v in FILES (Section 5.2.2: with NVMe offload the state is brought to

@@ -32,7 +32,7 @@ ZI_OPT_HOST_COPY_THREADS = 2
 EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
-    "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
+    "zi_grad_norm_streamed", "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
 ]
 
 
@@ -106,6 +106,9 @@ def lib() -> ctypes.CDLL:
         L.zi_adamw_step_streamed.restype = ctypes.c_int
         L.zi_adamw_step_streamed.argtypes = [vp, ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
                                              ctypes.POINTER(zi_adamw_config), vp, vp]
+        L.zi_grad_norm_streamed.restype = ctypes.c_int
+        L.zi_grad_norm_streamed.argtypes = [vp, ctypes.POINTER(zi_tensor), i32, ctypes.c_int, ctypes.c_float, vp, vp,
+                                            sz, vp]
         L.zi_adamw_step_files.restype = ctypes.c_int
         L.zi_adamw_step_files.argtypes = [vp, ctypes.POINTER(zi_file_tensor), i32, ctypes.c_int,
                                           ctypes.POINTER(zi_adamw_config), vp, vp]
@@ -226,6 +229,15 @@ def zi_adamw_step_streamed(engine, tensors, dt: int, cfg: zi_adamw_config, d_nor
     return _check(lib().zi_adamw_step_streamed(engine, arr, n, int(dt),
                                                ctypes.byref(cfg) if cfg is not None else None,
                                                _addr(d_norm), _stream(stream)))
+
+
+def zi_grad_norm_streamed(engine, tensors, dt: int, loss_scale: float, d_out, d_workspace,
+                          workspace_bytes: Optional[int] = None, stream=None) -> int:
+    arr, n = _as_tensor_array(tensors)
+    if workspace_bytes is None:
+        workspace_bytes = d_workspace.numel() * d_workspace.element_size()
+    return _check(lib().zi_grad_norm_streamed(engine, arr, n, int(dt), float(loss_scale), _addr(d_out),
+                                              _addr(d_workspace), int(workspace_bytes), _stream(stream)))
 
 
 def make_file_tensors(items):

@@ -179,6 +179,103 @@ struct StepIssuer {
     }
 };
 
+zi_status check_norm_args(const zi_tensor* t, int32_t n_tensors, int dt, float loss_scale, zi_norm_result* d_out,
+                          void* d_workspace, size_t workspace_bytes)
+{
+    if (zi_status st = check_dtype(dt)) return st;
+    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
+        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    if (!d_out) return fail(ZI_ERR_INVALID_ARG, "d_out is NULL");
+    if (!aligned(d_out, 8)) return fail(ZI_ERR_ALIGNMENT, "d_out must be 8-byte aligned");
+    if (!d_workspace) return fail(ZI_ERR_INVALID_ARG, "d_workspace is NULL");
+    if (!aligned(d_workspace, 16)) return fail(ZI_ERR_ALIGNMENT, "d_workspace must be 16-byte aligned");
+    if (workspace_bytes < (size_t)zi::kMaxPartials * sizeof(zi::NormPartial))
+        return fail(ZI_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes,
+                    (size_t)zi::kMaxPartials * sizeof(zi::NormPartial));
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+        if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
+        if (!aligned(t[i].g, 2)) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
+    }
+
+    return ZI_OK;
+}
+
+// Issues the gradient reduction over a list of device-resident gradient arrays: partial-sum launches
+// of up to kMaxNormDesc tensors, and a finalize pass whenever the workspace's partial slots run out
+// and at finish().  After the first finalize the later ones add to the result already in d_out.
+struct NormIssuer {
+    // A workgroup covers at least four tile iterations of its tensor; at most kBlocksPerTensor
+    // workgroups walk one tensor, so the partial count stays small whatever the size.
+    static constexpr int64_t kMinElemsPerBlock = 4 * zi::kNormTileElems;
+    static constexpr int64_t kBlocksPerTensor = 4096;
+
+    zi::NormArgs a{};
+    uint32_t blocks = 0;       // blocks of the launch being assembled
+    uint32_t used = 0;         // partials written since the last finalize
+    int finalized = 0;
+    int dt;
+    float loss_scale;
+    zi_norm_result* d_out;
+    hipStream_t s;
+
+    NormIssuer(zi::NormPartial* partials, int dt_, float ls, zi_norm_result* out, hipStream_t st)
+        : dt(dt_), loss_scale(ls), d_out(out), s(st)
+    {
+        a.partials = partials;
+        a.partial_base = 0;
+        a.n_desc = 0;
+    }
+    hipError_t flush_launch()
+    {
+        hipError_t e = hipSuccess;
+        if (a.n_desc > 0) e = zi::launch_norm_partials(a, blocks, dt, s);
+        used += blocks;
+        a.partial_base = used;
+        a.n_desc = 0;
+        blocks = 0;
+        return e;
+    }
+    hipError_t flush_partials()
+    {
+        hipError_t e = zi::launch_norm_finalize(a.partials, used, loss_scale, finalized, d_out, s);
+        finalized = 1;
+        used = 0;
+        a.partial_base = 0;
+        return e;
+    }
+    hipError_t add(const uint16_t* g, int64_t n)
+    {
+        if (n <= 0) return hipSuccess;
+        int64_t nb = (n + kMinElemsPerBlock - 1) / kMinElemsPerBlock;
+        if (nb > kBlocksPerTensor) nb = kBlocksPerTensor;
+        hipError_t e = hipSuccess;
+        if (a.n_desc == zi::kMaxNormDesc && (e = flush_launch()) != hipSuccess) return e;
+        if ((uint64_t)used + blocks + (uint64_t)nb > zi::kMaxPartials) {
+            if ((e = flush_launch()) != hipSuccess) return e;
+            if ((e = flush_partials()) != hipSuccess) return e;
+        }
+        zi::NormDesc d{};
+        d.g = g;
+        d.numel = n;
+        const int h = (int)((8 - (reinterpret_cast<uintptr_t>(g) / 2) % 8) % 8);
+        d.head = (int32_t)(h < n ? h : n);
+        d.first_block = blocks;
+        d.n_blocks = (uint32_t)nb;
+        a.t[a.n_desc++] = d;
+        blocks += (uint32_t)nb;
+        return hipSuccess;
+    }
+    hipError_t finish()
+    {
+        hipError_t e = flush_launch();
+        if (e != hipSuccess) return e;
+        return flush_partials();
+    }
+};
+
 }  // namespace
 
 // ============================================================================ plain queries
@@ -196,79 +293,11 @@ extern "C" zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_d
                                   zi_norm_result* d_out, void* d_workspace, size_t workspace_bytes,
                                   void* hip_stream)
 {
-    if (zi_status st = check_dtype((int)dt)) return st;
-    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
-    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
-    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
-        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
-    if (!d_out) return fail(ZI_ERR_INVALID_ARG, "d_out is NULL");
-    if (!aligned(d_out, 8)) return fail(ZI_ERR_ALIGNMENT, "d_out must be 8-byte aligned");
-    if (!d_workspace) return fail(ZI_ERR_INVALID_ARG, "d_workspace is NULL");
-    if (!aligned(d_workspace, 16)) return fail(ZI_ERR_ALIGNMENT, "d_workspace must be 16-byte aligned");
-    if (workspace_bytes < zi_norm_workspace_bytes(0, 0))
-        return fail(ZI_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes,
-                    zi_norm_workspace_bytes(0, 0));
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-        if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
-        if (!aligned(t[i].g, 2)) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
-    }
+    if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, d_workspace, workspace_bytes)) return st;
 
-    hipStream_t s = (hipStream_t)hip_stream;
-    zi::NormPartial* partials = (zi::NormPartial*)d_workspace;
-
-    // A workgroup covers at least four tile iterations of its tensor; at most kBlocksPerTensor
-    // workgroups walk one tensor, so the partial count stays small whatever the size.
-    constexpr int64_t kMinElemsPerBlock = 4 * zi::kNormTileElems;
-    constexpr int64_t kBlocksPerTensor = 4096;
-
-    zi::NormArgs a{};
-    a.partials = partials;
-    a.partial_base = 0;
-    a.n_desc = 0;
-    uint32_t blocks = 0;       // blocks of the launch being assembled
-    uint32_t used = 0;         // partials written since the last finalize
-    int finalized = 0;
-
-    auto flush_launch = [&]() -> hipError_t {
-        hipError_t e = hipSuccess;
-        if (a.n_desc > 0) e = zi::launch_norm_partials(a, blocks, (int)dt, s);
-        used += blocks;
-        a.partial_base = used;
-        a.n_desc = 0;
-        blocks = 0;
-        return e;
-    };
-    auto flush_partials = [&]() -> hipError_t {
-        hipError_t e = zi::launch_norm_finalize(partials, used, loss_scale, finalized, d_out, s);
-        finalized = 1;
-        used = 0;
-        a.partial_base = 0;
-        return e;
-    };
-
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        const int64_t n = t[i].numel;
-        if (n == 0) continue;
-        int64_t nb = (n + kMinElemsPerBlock - 1) / kMinElemsPerBlock;
-        if (nb > kBlocksPerTensor) nb = kBlocksPerTensor;
-        if (a.n_desc == zi::kMaxNormDesc) ZI_HIP(flush_launch());
-        if ((uint64_t)used + blocks + (uint64_t)nb > zi::kMaxPartials) {
-            ZI_HIP(flush_launch());
-            ZI_HIP(flush_partials());
-        }
-        zi::NormDesc d{};
-        d.g = (const uint16_t*)t[i].g;
-        d.numel = n;
-        const int h = (int)((8 - (reinterpret_cast<uintptr_t>(t[i].g) / 2) % 8) % 8);
-        d.head = (int32_t)(h < n ? h : n);
-        d.first_block = blocks;
-        d.n_blocks = (uint32_t)nb;
-        a.t[a.n_desc++] = d;
-        blocks += (uint32_t)nb;
-    }
-    ZI_HIP(flush_launch());
-    ZI_HIP(flush_partials());   // also writes zeros for an empty list
+    NormIssuer issue((zi::NormPartial*)d_workspace, (int)dt, loss_scale, d_out, (hipStream_t)hip_stream);
+    for (int32_t i = 0; i < n_tensors; ++i) ZI_HIP(issue.add((const uint16_t*)t[i].g, t[i].numel));
+    ZI_HIP(issue.finish());   // also writes zeros for an empty list
     return ZI_OK;
 }
 
@@ -501,6 +530,9 @@ private:
 };
 
 constexpr int kMaxHostSlots = 16;
+// A slot holds p, m, v and a fourth array whose first half stages host-resident gradients and whose
+// second half stages a host-resident low-precision copy.
+constexpr int kSlotArrays = 4;
 
 }  // namespace
 
@@ -515,14 +547,14 @@ struct zi_engine {
     CopyPool* pool_out = nullptr;
     float* hslot_array(int hslot, int which) const
     {
-        return reinterpret_cast<float*>(hring + ((size_t)hslot * 3 + which) * array_bytes);
+        return reinterpret_cast<float*>(hring + ((size_t)hslot * kSlotArrays + which) * array_bytes);
     }
     int device = 0;
     size_t chunk_bytes = 0;
     int64_t chunk_elems = 0;
     int n_slots = 0;
     size_t array_bytes = 0;            // chunk_bytes + room for phase lead-in
-    char* staging = nullptr;           // n_slots * 3 * array_bytes
+    char* staging = nullptr;           // n_slots * kSlotArrays * array_bytes
     hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
     hipEvent_t ev_h2d[8] = {}, ev_k[8] = {}, ev_d2h[8] = {};
     hipEvent_t ev_in = nullptr, ev_out = nullptr;
@@ -531,9 +563,19 @@ struct zi_engine {
     zi_stream_stats stats{};
     uint32_t magic = 0;
 
+    uint16_t* slot_g(int slot) const { return reinterpret_cast<uint16_t*>(slot_array(slot, 3)); }
+    uint16_t* slot_lp(int slot) const
+    {
+        return reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(slot_array(slot, 3)) + array_bytes / 2);
+    }
+    uint16_t* hslot_g(int h) const { return reinterpret_cast<uint16_t*>(hslot_array(h, 3)); }
+    uint16_t* hslot_lp(int h) const
+    {
+        return reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(hslot_array(h, 3)) + array_bytes / 2);
+    }
     float* slot_array(int slot, int which) const
     {
-        return reinterpret_cast<float*>(staging + ((size_t)slot * 3 + which) * array_bytes);
+        return reinterpret_cast<float*>(staging + ((size_t)slot * kSlotArrays + which) * array_bytes);
     }
 };
 
@@ -619,7 +661,7 @@ extern "C" zi_status zi_engine_create(zi_engine** out, int32_t device, size_t ch
         }                                                                                        \
     } while (0)
 
-    ZI_HIP_E(hipMalloc((void**)&e->staging, (size_t)n_slots * 3 * e->array_bytes));
+    ZI_HIP_E(hipMalloc((void**)&e->staging, (size_t)n_slots * kSlotArrays * e->array_bytes));
     ZI_HIP_E(hipHostMalloc((void**)&e->h_norm, sizeof(zi_norm_result), hipHostMallocDefault));
     ZI_HIP_E(hipStreamCreateWithFlags(&e->s_h2d, hipStreamNonBlocking));
     ZI_HIP_E(hipStreamCreateWithFlags(&e->s_k, hipStreamNonBlocking));
@@ -682,7 +724,7 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
         ZI_HIP(hipSetDevice(e->device));
         ring_release(e);
         if (value == 0) return ZI_OK;
-        hipError_t he = hipHostMalloc((void**)&e->hring, (size_t)value * 3 * e->array_bytes, hipHostMallocDefault);
+        hipError_t he = hipHostMalloc((void**)&e->hring, (size_t)value * kSlotArrays * e->array_bytes, hipHostMallocDefault);
         if (he != hipSuccess) {
             e->hring = nullptr;
             (void)hipGetLastError();
@@ -720,10 +762,27 @@ struct StateSrc {
     int fd[3];           // file kind
     int64_t off[3];
     bool direct[3];      // descriptor was opened with O_DIRECT
-    const void* g;       // device
-    void* p_lp;          // device, may be null
+    const void* g;       // device, or host when g_host
+    void* p_lp;          // device, or host when lp_host; may be null
+    bool g_host;         // gradients live in host memory and are staged chunk by chunk
+    bool lp_host;        // the low-precision copy is written back to host memory
     int64_t numel;
 };
+
+// Device, page-locked host or ordinary host memory?  (0, 1, 2; -1 for anything else.)
+int memory_kind(const void* p)
+{
+    hipPointerAttribute_t attr{};
+    const hipError_t pe = hipPointerGetAttributes(&attr, p);
+    if (pe != hipSuccess) {
+        (void)hipGetLastError();
+        return 2;
+    }
+    if (attr.type == hipMemoryTypeDevice) return 0;
+    if (attr.type == hipMemoryTypeHost) return 1;
+    if (attr.type == hipMemoryTypeUnregistered) return 2;
+    return -1;
+}
 
 // The chunk pipeline.  `staged` = the state is not page-locked memory and travels through the
 // engine's pinned ring (CPU threads fill and empty the ring slots).
@@ -765,9 +824,13 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
 
     // Where a segment sits inside a slot (HBM slot and pinned-ring slot share one layout).
     auto slot_off = [&](const Segment& sg) -> int64_t {
-        const uint16_t* g = (const uint16_t*)src[(size_t)sg.tensor].g + sg.elem_offset;
-        // Lead-in elements that give the staged fp32 arrays the alignment phase of the gradients.
-        return sg.slot_offset + (int64_t)((reinterpret_cast<uintptr_t>(g) / 2) % 4);
+        // Lead-in elements that give the staged arrays the alignment phase of the device-resident
+        // 2-byte array the kernel will see beside them (gradients, else the low-precision copy).
+        const StateSrc& S = src[(size_t)sg.tensor];
+        const uint16_t* ref = nullptr;
+        if (!S.g_host) ref = (const uint16_t*)S.g + sg.elem_offset;
+        else if (S.p_lp && !S.lp_host) ref = (const uint16_t*)S.p_lp + sg.elem_offset;
+        return sg.slot_offset + (ref ? (int64_t)((reinterpret_cast<uintptr_t>(ref) / 2) % 4) : 0);
     };
     // Transfer lists between the caller's state (ordinary memory or files) and ring slot h for one
     // slot use.  Direct-I/O files move whole 4096-byte blocks: the rounded-up tail of a region is read
@@ -777,6 +840,19 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
         for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
             const Segment& sg = segs[j];
             const StateSrc& S = src[(size_t)sg.tensor];
+            auto mem_pieces = [&](char* ring, char* user_mem, size_t bytes) {
+                for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
+                    const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
+                    if (inbound) out.push_back({0, ring + o, user_mem + o, -1, 0, nb, nb, false});
+                    else         out.push_back({0, user_mem + o, ring + o, -1, 0, nb, nb, false});
+                }
+            };
+            if (inbound && S.g_host)
+                mem_pieces((char*)(e->hslot_g(h) + slot_off(sg)), (char*)S.g + sg.elem_offset * 2,
+                           (size_t)sg.count * 2);
+            if (!inbound && S.lp_host && S.p_lp)
+                mem_pieces((char*)(e->hslot_lp(h) + slot_off(sg)), (char*)S.p_lp + sg.elem_offset * 2,
+                           (size_t)sg.count * 2);
             for (int w = 0; w < 3; ++w) {
                 char* rp = (char*)(e->hslot_array(h, w) + slot_off(sg));
                 const size_t need = (size_t)sg.count * 4;
@@ -887,7 +963,8 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
             // Waiting for the OLDEST slot use keeps the host n_slots uses ahead of the copy engines.
             if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_d2h[slot]));
 
-            struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes; };
+            struct Placed { float *dp, *dm, *dv; char *hp, *hm, *hv; size_t bytes;
+                            const uint16_t* g; uint16_t* lp; char* lp_host; size_t lp_bytes; };
             Placed placed[zi::kMaxStepDesc];
             StepIssuer issue(k, d_norm, (int)dt, l2, e->s_k);
             int np = 0;
@@ -909,6 +986,25 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
                     P.hv = T.ptr[2] + sg.elem_offset * 4;
                 }
                 P.bytes = (size_t)sg.count * 4;
+                // 2-byte arrays: used in place when device-resident, staged in the slot otherwise
+                P.g = (const uint16_t*)T.g + sg.elem_offset;
+                if (T.g_host) {
+                    const char* hg = staged ? (const char*)(e->hslot_g(h) + so) : (const char*)T.g + sg.elem_offset * 2;
+                    ZI_HIP(hipMemcpyAsync(e->slot_g(slot) + so, hg, (size_t)sg.count * 2, hipMemcpyHostToDevice,
+                                          e->s_h2d));
+                    P.g = e->slot_g(slot) + so;
+                    e->stats.bytes_h2d += (size_t)sg.count * 2;
+                    e->stats.n_copies += 1;
+                    if (staged) staged_bytes += (size_t)sg.count * 2;
+                }
+                P.lp = T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr;
+                P.lp_host = nullptr;
+                P.lp_bytes = 0;
+                if (T.p_lp && T.lp_host) {
+                    P.lp = e->slot_lp(slot) + so;
+                    P.lp_host = staged ? (char*)(e->hslot_lp(h) + so) : (char*)T.p_lp + sg.elem_offset * 2;
+                    P.lp_bytes = (size_t)sg.count * 2;
+                }
                 ZI_HIP(hipMemcpyAsync(P.dp, P.hp, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
                 ZI_HIP(hipMemcpyAsync(P.dm, P.hm, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
                 ZI_HIP(hipMemcpyAsync(P.dv, P.hv, P.bytes, hipMemcpyHostToDevice, e->s_h2d));
@@ -923,10 +1019,8 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
                 np = 0;
                 for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
                     const Segment& sg = segs[j];
-                    const StateSrc& T = src[(size_t)sg.tensor];
-                    ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv,
-                                     (const uint16_t*)T.g + sg.elem_offset,
-                                     T.p_lp ? (uint16_t*)T.p_lp + sg.elem_offset : nullptr, sg.count));
+                    ZI_HIP(issue.add(placed[np].dp, placed[np].dm, placed[np].dv, placed[np].g, placed[np].lp,
+                                     sg.count));
                 }
                 ZI_HIP(issue.flush());
                 e->stats.n_kernels += issue.launches;
@@ -941,6 +1035,12 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
                 ZI_HIP(hipMemcpyAsync(P.hv, P.dv, P.bytes, hipMemcpyDeviceToHost, e->s_d2h));
                 e->stats.bytes_d2h += 3 * P.bytes;
                 e->stats.n_copies += 3;
+                if (P.lp_host) {
+                    ZI_HIP(hipMemcpyAsync(P.lp_host, P.lp, P.lp_bytes, hipMemcpyDeviceToHost, e->s_d2h));
+                    e->stats.bytes_d2h += P.lp_bytes;
+                    e->stats.n_copies += 1;
+                    if (staged) staged_bytes += P.lp_bytes;
+                }
             }
             ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
             if (staged) {
@@ -996,38 +1096,197 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
 
     // State that is not page-locked cannot feed the copy engines directly (a pageable source turns
     // every copy into a staged, synchronous one).  It goes through the engine's pinned ring if one
-    // has been set up, otherwise it is refused.
+    // has been set up, otherwise it is refused.  Gradients and the low-precision copy may live on
+    // the device (used in place) or in host memory (staged with the state, chunk by chunk).
     bool pageable = false;
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        if (t[i].numel == 0) continue;
-        const void* arrs[3] = {t[i].p, t[i].m, t[i].v};
-        for (const void* a : arrs) {
-            hipPointerAttribute_t attr{};
-            hipError_t pe = hipPointerGetAttributes(&attr, a);
-            if (pe != hipSuccess || attr.type != hipMemoryTypeHost) {
-                (void)hipGetLastError();
-                if (pe == hipSuccess && attr.type != hipMemoryTypeUnregistered)
-                    return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be host memory", i);
-                if (e->n_hslots == 0)
-                    return fail(ZI_ERR_INVALID_ARG,
-                                "tensor %d: p, m, v must be pinned host memory (or give the engine a pinned "
-                                "ring with ZI_OPT_HOST_RING_SLOTS)", i);
-                pageable = true;
-            }
-        }
-    }
-
     std::vector<StateSrc> src((size_t)n_tensors);
     for (int32_t i = 0; i < n_tensors; ++i) {
         StateSrc& S = src[(size_t)i];
-        S.kind = pageable ? kSrcPageable : kSrcPinned;
+        S.kind = kSrcPinned;
         S.ptr[0] = (char*)t[i].p; S.ptr[1] = (char*)t[i].m; S.ptr[2] = (char*)t[i].v;
         S.fd[0] = S.fd[1] = S.fd[2] = -1;
         S.off[0] = S.off[1] = S.off[2] = 0;
         S.direct[0] = S.direct[1] = S.direct[2] = false;
         S.g = t[i].g; S.p_lp = t[i].p_lp; S.numel = t[i].numel;
+        S.g_host = S.lp_host = false;
+        if (t[i].numel == 0) continue;
+        for (int w = 0; w < 3; ++w) {
+            const int kind = memory_kind(S.ptr[w]);
+            if (kind != 1 && kind != 2) return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be host memory", i);
+            if (kind == 2) pageable = true;
+        }
+        const int gk = memory_kind(S.g);
+        if (gk < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is neither device nor host memory", i);
+        S.g_host = gk != 0;
+        if (gk == 2) pageable = true;
+        if (S.p_lp) {
+            const int lk = memory_kind(S.p_lp);
+            if (lk < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: p_lp is neither device nor host memory", i);
+            S.lp_host = lk != 0;
+            if (lk == 2) pageable = true;
+        }
+    }
+    if (pageable) {
+        if (e->n_hslots == 0)
+            return fail(ZI_ERR_INVALID_ARG, "host arrays must be pinned host memory (or give the engine a pinned "
+                                            "ring with ZI_OPT_HOST_RING_SLOTS)");
+        for (auto& S : src) S.kind = kSrcPageable;   // one path per call: everything host-side rides the ring
     }
     return run_streamed(e, src, pageable, dt, cfg, d_norm, user);
+}
+
+extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                                           float loss_scale, zi_norm_result* d_out, void* d_workspace,
+                                           size_t workspace_bytes, void* hip_stream)
+{
+    if (zi_status st = check_engine(e)) return st;
+    if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, d_workspace, workspace_bytes)) return st;
+    ZI_HIP(hipSetDevice(e->device));
+    hipStream_t user = (hipStream_t)hip_stream;
+    e->stats = zi_stream_stats{};
+
+    // Device-resident gradients are reduced in place; host-resident ones are staged chunk by chunk.
+    std::vector<int32_t> host_idx;
+    std::vector<int64_t> host_numel;
+    bool pageable = false;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (t[i].numel == 0) continue;
+        const int k = memory_kind(t[i].g);
+        if (k < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is neither device nor host memory", i);
+        if (k == 0) continue;
+        if (k == 2) pageable = true;
+        host_idx.push_back(i);
+        host_numel.push_back(t[i].numel);
+    }
+    if (pageable && e->n_hslots == 0)
+        return fail(ZI_ERR_INVALID_ARG, "host gradients must be pinned host memory (or give the engine a pinned "
+                                        "ring with ZI_OPT_HOST_RING_SLOTS)");
+    std::vector<Segment> segs;
+    int64_t n_uses = 0;
+    try {
+        plan_chunks(host_numel.data(), (int32_t)host_numel.size(), e->chunk_elems, segs, n_uses);
+    } catch (const std::bad_alloc&) {
+        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+    }
+    std::vector<size_t> use_begin((size_t)n_uses + 1, segs.size());
+    for (size_t j = segs.size(); j-- > 0;) use_begin[(size_t)segs[j].slot_use] = j;
+    for (int64_t u = n_uses - 1; u >= 0; --u)
+        if (use_begin[(size_t)u] > use_begin[(size_t)u + 1]) use_begin[(size_t)u] = use_begin[(size_t)u + 1];
+
+    ZI_HIP(hipEventRecord(e->ev_in, user));
+    ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
+    ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
+
+    const int n_h = e->n_hslots;
+    struct {
+        std::mutex mu;
+        std::condition_variable cv;
+        int64_t gathered = 0, issued = 0;
+        bool abort = false;
+    } sync;
+    std::thread gather_thread;
+    if (pageable) {
+        gather_thread = std::thread([&] {
+            (void)hipSetDevice(e->device);
+            std::vector<CopyPool::Piece> pieces;
+            for (int64_t u = 0; u < n_uses; ++u) {
+                const int h = (int)(u % n_h);
+                if (u >= n_h) {      // the ring slot is free once its previous host-to-device copies are done
+                    std::unique_lock<std::mutex> lk(sync.mu);
+                    sync.cv.wait(lk, [&] { return sync.abort || sync.issued > u - n_h; });
+                    if (sync.abort) return;
+                    lk.unlock();
+                    if (hipEventSynchronize(e->ev_back[h]) != hipSuccess) {
+                        (void)hipGetLastError();
+                        std::lock_guard<std::mutex> lk2(sync.mu);
+                        sync.abort = true;
+                        sync.cv.notify_all();
+                        return;
+                    }
+                }
+                pieces.clear();
+                for (size_t j = use_begin[(size_t)u]; j < use_begin[(size_t)u + 1]; ++j) {
+                    const Segment& sg = segs[j];
+                    char* ring = (char*)(e->hslot_g(h) + sg.slot_offset);
+                    const char* um = (const char*)t[host_idx[(size_t)sg.tensor]].g + sg.elem_offset * 2;
+                    const size_t bytes = (size_t)sg.count * 2;
+                    for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
+                        const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
+                        pieces.push_back({0, ring + o, um + o, -1, 0, nb, nb, false});
+                    }
+                }
+                e->pool_in->run(pieces);
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    sync.gathered = u + 1;
+                }
+                sync.cv.notify_all();
+            }
+        });
+    }
+
+    const auto t0 = std::chrono::steady_clock::now();
+    uint64_t staged_bytes = 0;
+    auto pipeline = [&]() -> zi_status {
+        NormIssuer issue((zi::NormPartial*)d_workspace, (int)dt, loss_scale, d_out, e->s_k);
+        for (int32_t i = 0; i < n_tensors; ++i)
+            if (t[i].numel > 0 && memory_kind(t[i].g) == 0) ZI_HIP(issue.add((const uint16_t*)t[i].g, t[i].numel));
+        for (int64_t use = 0; use < n_uses; ++use) {
+            const int slot = (int)(use % e->n_slots);
+            const int h = pageable ? (int)(use % n_h) : 0;
+            if (pageable) {
+                std::unique_lock<std::mutex> lk(sync.mu);
+                sync.cv.wait(lk, [&] { return sync.abort || sync.gathered > use; });
+                if (sync.abort) return fail(ZI_ERR_HIP, "waiting for the pinned ring failed");
+            }
+            // the slot's staged gradients are free once the reduction that last read them is done
+            if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_k[slot]));
+            for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
+                const Segment& sg = segs[j];
+                const char* hg = pageable ? (const char*)(e->hslot_g(h) + sg.slot_offset)
+                                          : (const char*)t[host_idx[(size_t)sg.tensor]].g + sg.elem_offset * 2;
+                ZI_HIP(hipMemcpyAsync(e->slot_g(slot) + sg.slot_offset, hg, (size_t)sg.count * 2,
+                                      hipMemcpyHostToDevice, e->s_h2d));
+                e->stats.bytes_h2d += (size_t)sg.count * 2;
+                e->stats.n_copies += 1;
+                if (pageable) staged_bytes += (size_t)sg.count * 2;
+            }
+            ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
+            if (pageable) {
+                ZI_HIP(hipEventRecord(e->ev_back[h], e->s_h2d));
+                {
+                    std::lock_guard<std::mutex> lk(sync.mu);
+                    sync.issued = use + 1;
+                }
+                sync.cv.notify_all();
+            }
+            ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
+            for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j)
+                ZI_HIP(issue.add(e->slot_g(slot) + segs[j].slot_offset, segs[j].count));
+            ZI_HIP(issue.finish());      // the staged chunk is consumed before its slot is reused
+            e->stats.n_kernels += 2;
+            ZI_HIP(hipEventRecord(e->ev_k[slot], e->s_k));
+            ++e->stats.n_slot_uses;
+        }
+        if (n_uses == 0) ZI_HIP(issue.finish());
+        ZI_HIP(hipEventRecord(e->ev_out, e->s_k));
+        ZI_HIP(hipStreamWaitEvent(user, e->ev_out, 0));
+        ZI_HIP(hipStreamSynchronize(e->s_k));
+        return ZI_OK;
+    };
+    zi_status st = pipeline();
+    if (pageable) {
+        if (st != ZI_OK) {
+            std::lock_guard<std::mutex> lk(sync.mu);
+            sync.abort = true;
+        }
+        sync.cv.notify_all();
+        gather_thread.join();
+        if (st == ZI_OK && sync.abort) st = fail(ZI_ERR_HIP, "the pinned ring's copy thread failed");
+    }
+    e->stats.bytes_staged_host = staged_bytes;
+    e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    return st;
 }
 
 extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
@@ -1051,6 +1310,7 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
         S.fd[0] = t[i].fd_p; S.fd[1] = t[i].fd_m; S.fd[2] = t[i].fd_v;
         S.off[0] = t[i].off_p; S.off[1] = t[i].off_m; S.off[2] = t[i].off_v;
         S.g = t[i].g; S.p_lp = t[i].p_lp; S.numel = t[i].numel;
+        S.g_host = S.lp_host = false;
         if (S.numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
         if (S.numel == 0) continue;
         if (!S.g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
@@ -1086,7 +1346,7 @@ extern "C" zi_status zi_engine_file_probe(zi_engine* e, int32_t fd_read, int32_t
     if (bytes == 0 || bytes % 4096) return fail(ZI_ERR_INVALID_ARG, "bytes must be a positive multiple of 4096");
     if (e->n_hslots < 2) return fail(ZI_ERR_INVALID_ARG, "ring too small");
     // Reads land in the first half of the ring, writes leave from the second half.
-    const size_t half = (size_t)(e->n_hslots / 2) * 3 * e->array_bytes / 4096 * 4096;
+    const size_t half = (size_t)(e->n_hslots / 2) * kSlotArrays * e->array_bytes / 4096 * 4096;
     auto pieces_for = [&](int fd, int op, char* base, std::vector<CopyPool::Piece>& out) {
         const int fl = fcntl(fd, F_GETFL);
         const bool direct = fl >= 0 && (fl & O_DIRECT);

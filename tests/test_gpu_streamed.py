@@ -183,6 +183,104 @@ def test_pageable_state_through_the_pinned_ring(hslots, threads):
         zi.zi_engine_destroy(eng)
 
 
+def _pinned16(a: np.ndarray) -> torch.Tensor:
+    t = torch.empty(a.size, dtype=torch.int16, pin_memory=True)
+    t.numpy()[:] = a.view(np.int16)
+    return t
+
+
+@pytest.mark.parametrize("placement", ["g_pinned", "lp_pinned", "both_pinned", "all_pageable", "g_pageable_state_pinned"])
+def test_gradients_and_copy_in_host_memory(placement):
+    """Gradient-side offload: gradients and / or the low-precision copy live in host memory and travel with
+    their chunk of state; the norm is reduced from host-resident gradients too.  Same bits as resident."""
+    w = zi_synth.workload("c4")
+    dt = zi.ZI_BF16
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 4)
+        h = 128
+        for numel in ([7 * 16384 + 4322], [n for _ in range(2) for (_, n) in zi_synth.transformer_layer_shapes(h)]):
+            spec = zi_synth.StateSpec(99 + len(numel), dt, g_std=2e-3)
+            host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(numel)]
+            ocfg, zcfg = oracle_cfg(w), zi_cfg(w)
+            exp = [(p.copy(), m.copy(), v.copy(), g, np.zeros(p.size, np.uint16)) for (p, m, v, g) in host]
+            info = oracle.step(exp, dt, ocfg, use_norm=True)
+            tl, keep = [], []
+            for (p, m, v, g) in host:
+                if placement == "all_pageable":
+                    sp, sm, sv = p.copy(), m.copy(), v.copy()
+                    sg, slp = g.copy(), np.zeros(g.size, np.uint16)
+                else:
+                    sp, sm, sv = _pinned(p), _pinned(m), _pinned(v)
+                    sg = to_dev(g)
+                    slp = torch.zeros(g.size, dtype=torch.int16, device="cuda:0")
+                    if placement in ("g_pinned", "both_pinned"):
+                        sg = _pinned16(g)
+                    if placement == "g_pageable_state_pinned":
+                        sg = g.copy()
+                    if placement in ("lp_pinned", "both_pinned"):
+                        slp = torch.zeros(g.size, dtype=torch.int16, pin_memory=True)
+                keep.append((sp, sm, sv, sg, slp))
+                tl.append((sp, sm, sv, sg, slp, g.size))
+            nb = NormBuffers()
+            zi.zi_grad_norm_streamed(eng, tl, dt, ocfg.loss_scale, nb.out, nb.ws, stream=torch.cuda.current_stream())
+            sumsq, norm, flag = nb.read()
+            assert flag == 0 and abs(sumsq - info["sumsq"]) <= 1e-12 * info["sumsq"]
+            st = zi.zi_adamw_step_streamed(eng, tl, dt, zcfg, nb.out, torch.cuda.current_stream())
+            assert st == zi.ZI_OK
+            stats = zi.zi_engine_last_stats(eng)
+            g_host = placement != "lp_pinned"
+            lp_host = placement in ("lp_pinned", "both_pinned", "all_pageable")
+            assert stats.bytes_h2d == (12 + 2 * g_host) * sum(numel)
+            assert stats.bytes_d2h == (12 + 2 * lp_host) * sum(numel)
+            as_np = lambda x: x if isinstance(x, np.ndarray) else (x.numpy() if x.device.type == "cpu" else to_np(x))
+            for e, (sp, sm, sv, sg, slp) in zip(exp, keep):
+                got = (as_np(sp), as_np(sm), as_np(sv), as_np(slp).view(np.uint16))
+                compare_state((e[0], e[1], e[2], e[4]), got, dt, f"{placement} ")
+                assert np.array_equal(got[0].view(np.uint32), e[0].view(np.uint32))     # in fact bit-identical
+    finally:
+        zi.zi_engine_destroy(eng)
+
+
+def test_streamed_norm_flags_and_mixed_residency():
+    dt = zi.ZI_FP16
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 3)
+        sizes = [5 * 32768 + 77, 1000, 0, 40000, 3]
+        gs = []
+        for i, n in enumerate(sizes):
+            g = np.empty(n, np.uint16)
+            zi_synth.fill_normal_lp(g, n, 5 + i, zi_synth.STREAM_G, dt, std=50.0)
+            gs.append(g)
+        want, _ = oracle.grad_sumsq(gs, dt)
+        # device, pinned, empty, ordinary, ordinary
+        placed = [to_dev(gs[0]), _pinned16(gs[1]), None, gs[3].copy(), gs[4].copy()]
+        tl = [(None, None, None, x, None, n) for x, n in zip(placed, sizes)]
+        nb = NormBuffers()
+        zi.zi_grad_norm_streamed(eng, tl, dt, 8.0, nb.out, nb.ws)
+        sumsq, norm, flag = nb.read()
+        assert flag == 0 and abs(sumsq - want) <= 1e-12 * want and abs(norm - np.sqrt(want) / 8.0) <= 1e-9 * norm
+        placed[3][12345] = 0x7C00                     # +inf in an ordinary-memory tensor
+        zi.zi_grad_norm_streamed(eng, tl, dt, 8.0, nb.out, nb.ws)
+        assert nb.read()[2] == 1
+        placed[3][12345] = 0
+        p1 = _pinned16(gs[1])
+        p1[999] = -1                                   # 0xFFFF: NaN in a pinned tensor's last element
+        tl[1] = (None, None, None, p1, None, sizes[1])
+        zi.zi_grad_norm_streamed(eng, tl, dt, 8.0, nb.out, nb.ws)
+        assert nb.read()[2] == 1
+        # all-empty list gives zeros
+        zi.zi_grad_norm_streamed(eng, [], dt, 1.0, nb.out, nb.ws)
+        assert nb.read() == (0.0, 0.0, 0)
+        # ordinary-memory gradients without a ring are refused
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 0)
+        with pytest.raises(zi.ZiError):
+            zi.zi_grad_norm_streamed(eng, tl, dt, 8.0, nb.out, nb.ws)
+    finally:
+        zi.zi_engine_destroy(eng)
+
+
 def _write_state_files(tmp, host, direct):
     """One file per array kind; tensor i of the list starts at a 4096-byte aligned offset."""
     offs, pos = [], 0
