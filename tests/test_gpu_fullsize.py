@@ -316,6 +316,55 @@ def test_file_tier_one_gibi_elements_direct_io():
                 zi.zi_engine_destroy(eng)
 
 
+def test_everything_offloaded_one_gibi_elements():
+    """All five arrays in pinned host memory (16 GiB): norm reduced from host-resident gradients, then the
+    step with gradients travelling in and the low-precision copy travelling out with each chunk."""
+    w = zi_synth.workload("c2")
+    n, dt, spec = 1 << 30, w["lp_dtype"], w["spec"]
+    chunk = w["chunk_bytes"] // 4
+    hp, hm, hv = PinnedF32(n), PinnedF32(n), PinnedF32(n)
+    hg = torch.empty(n, dtype=torch.int16, pin_memory=True)
+    hlp = torch.zeros(n, dtype=torch.int16, pin_memory=True)
+    eng = None
+    try:
+        spec.fill_p(hp.np, n)
+        spec.fill_m(hm.np, n)
+        spec.fill_v(hv.np, n)
+        spec.fill_g(hg, n)
+        progress("offload: state, gradients and copy in pinned host memory")
+        eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
+        tl = [(hp.ptr, hm.ptr, hv.ptr, hg, hlp, n)]
+        nb = NormBuffers()
+        cfg = dict(max_grad_norm=1.0)
+        zi.zi_grad_norm_streamed(eng, tl, dt, 1.0, nb.out, nb.ws, stream=torch.cuda.current_stream())
+        ns = zi.zi_engine_last_stats(eng)
+        sumsq, norm, flag = nb.read()
+        progress(f"offload: norm pass {ns.seconds * 1e3:.1f} ms = {2 * n / ns.seconds / 1e9:.1f} GB/s over the link")
+        st = zi.zi_adamw_step_streamed(eng, tl, dt, zi_cfg(w, **cfg), nb.out, torch.cuda.current_stream())
+        assert st == zi.ZI_OK
+        stats = zi.zi_engine_last_stats(eng)
+        assert stats.bytes_h2d == 14 * n == stats.bytes_d2h
+        progress(f"offload: step in {stats.seconds:.3f} s = {14 * n / stats.seconds / 1e9:.1f} GB/s per direction")
+        osumsq, oflag = oracle.grad_sumsq([hg.numpy().view(np.uint16)], dt)
+        assert flag == oflag == 0 and abs(sumsq - osumsq) <= 1e-12 * osumsq
+        assert oracle.scalars(oracle_cfg(w, **cfg), osumsq).clip < 0.04
+        ranges = sample_ranges(n, WIDTH, extra_points=(chunk, 2 * chunk, 3 * chunk), count=6, seed=9)
+        worst = ""
+        lp_np = hlp.numpy().view(np.uint16)
+        for lo, hi in ranges:
+            exp = oracle_range(spec, dt, oracle_cfg(w, **cfg), lo, hi, sumsq=osumsq)
+            got = (hp.np[lo:hi].copy(), hm.np[lo:hi].copy(), hv.np[lo:hi].copy(), lp_np[lo:hi].copy())
+            worst = compare_state(exp, got, dt, f"offload [{lo},{hi}) ")
+        want = torch.from_numpy(hp.np[:1 << 28]).to("cuda:0").to(torch.bfloat16).view(torch.int16).cpu()
+        assert torch.equal(want, hlp[:1 << 28])
+        progress(f"offload: norm {norm:.5f}; {len(ranges)} ranges verified; last: {worst}")
+    finally:
+        if eng is not None:
+            zi.zi_engine_destroy(eng)
+        for a in (hp, hm, hv):
+            a.free()
+
+
 def test_c4_ragged_transformer_layers_streamed_with_clip():
     w = zi_synth.workload("c4")
     numel, dt, spec = w["numel"], w["lp_dtype"], w["spec"]
