@@ -196,6 +196,35 @@ def streamed(args, torch, zi, zs):
             copy_only.append(zi.zi_engine_last_stats(eng).seconds)
         zi.zi_engine_set_option(eng, zi.ZI_OPT_SKIP_KERNEL, 0)
         st = zi.zi_engine_last_stats(eng)
+
+        # Gradient-side offload: gradients and the low-precision copy in pinned host memory as well
+        # (14 B/element each way), with the norm reduced from the host-resident gradients.
+        log("streamed: gradients and copy offloaded too")
+        hg = torch.empty(n, dtype=torch.int16, pin_memory=True)
+        hg.copy_(g)
+        hlp = torch.zeros(n, dtype=torch.int16, pin_memory=True)
+        d_norm = torch.zeros(3, dtype=torch.float64, device=dev)
+        ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device=dev)
+        tl_off = zi.make_tensors([(hp, hm, hv, hg, hlp, n)])
+        off_norm, off_step = [], []
+        for _ in range(3):
+            zi.zi_grad_norm_streamed(eng, tl_off, w["lp_dtype"], 1.0, d_norm, ws)
+            off_norm.append(zi.zi_engine_last_stats(eng).seconds)
+            zi.zi_adamw_step_streamed(eng, tl_off, w["lp_dtype"], cfg, d_norm)
+            off_step.append(zi.zi_engine_last_stats(eng).seconds)
+        del hg, hlp
+
+        # State in ordinary (not page-locked) host memory, through a 6-slot pinned ring.
+        log("streamed: ordinary host memory through the pinned ring")
+        op, om, ov = hp.numpy().copy(), hm.numpy().copy(), hv.numpy().copy()
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 7)
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 6)
+        tl_ring = zi.make_tensors([(op, om, ov, g, lp, n)])
+        ring = []
+        for _ in range(3):
+            zi.zi_adamw_step_streamed(eng, tl_ring, w["lp_dtype"], cfg)
+            ring.append(zi.zi_engine_last_stats(eng).seconds)
+        del op, om, ov
     finally:
         zi.zi_engine_destroy(eng)
     t = min(times)
@@ -206,7 +235,17 @@ def streamed(args, torch, zi, zs):
         measured_peak_GBps=dict((k, round(x, 2)) for k, x in peaks.items()),
         frac_of_bidir_peak=round(per_dir / peaks["bidir"], 4),
         hidden_ratio=round(t / min(copy_only), 4), copy_only_seconds=min(copy_only),
-        slot_uses=int(st.n_slot_uses))
+        slot_uses=int(st.n_slot_uses),
+        all_offloaded=dict(
+            what="p, m, v, gradients and copy in pinned host memory: 14 B/element each way",
+            step_GBps_per_direction=round(14 * n / min(off_step) / 1e9, 2),
+            step_frac_of_bidir_peak=round(14 * n / min(off_step) / 1e9 / peaks["bidir"], 4),
+            norm_GBps=round(2 * n / min(off_norm) / 1e9, 2),
+            norm_frac_of_h2d_peak=round(2 * n / min(off_norm) / 1e9 / peaks["h2d"], 4)),
+        ordinary_memory_ring=dict(
+            what="p, m, v in ordinary host memory, 6-slot pinned ring, 7 copy threads per direction",
+            GBps_per_direction=round(12 * n / min(ring) / 1e9, 2),
+            frac_of_bidir_peak=round(12 * n / min(ring) / 1e9 / peaks["bidir"], 4)))
 
 
 def cpu_baseline(args, zs):
