@@ -262,3 +262,20 @@ def test_every_fp32_pattern_through_the_copy(dt):
         if c % (1 << 30) == 0:
             progress(f"cast sweep dt={dt}: {c >> 27}/32 chunks, mismatches so far {bad}")
     assert bad == 0
+
+
+def test_device_reproduces_the_oracle_golden_file():
+    """The frozen oracle outputs under tests/golden/ (written by a script that calls only the oracle)."""
+    from golden_util import load_cases
+    for c in load_cases():
+        n = c["in_p"].size
+        p, m, v, g = (to_dev(c[k].copy()) for k in ("in_p", "in_m", "in_v", "in_g"))
+        lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+        nb = None
+        if c["use_norm"]:
+            nb = NormBuffers()
+            zi.zi_grad_norm([(None, None, None, g, None, n)], c["dtype"], c["kw"].get("loss_scale", 1.0), nb.out, nb.ws)
+        zi.zi_adamw_step([(p, m, v, g, lp, n)], c["dtype"], zi.make_config(**c["kw"]), None if nb is None else nb.out)
+        torch.cuda.synchronize()
+        compare_state((c["out_p"], c["out_m"], c["out_v"], c["out_lp"]), (to_np(p), to_np(m), to_np(v), to_np(lp)),
+                      c["dtype"], c["name"] + " ")
