@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libzi.so")
-SOURCES = ["zi_kernels.hip", "zi_api.hip"]
+SOURCES = ["zi_kernels.hip", "zi_api.hip", "zi_plan.hip", "zi_engine.hip"]
 
 # -ffp-contract=off: the only fused multiply-adds are the ones the kernels write as fma.
 # Packed fp32 instructions are switched off for the device code.

@@ -1,0 +1,277 @@
+// Host-side helpers shared by the C-ABI translation units: error reporting, argument checks,
+// per-step scalars, and the objects that assemble kernel launches over tensor lists.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <vector>
+
+#include "zi_internal.h"
+
+namespace zi {
+namespace host {
+
+// Stores the calling thread's error text (returned by zi_last_error) and passes the status through.
+zi_status fail(zi_status st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+const char* last_error();
+
+#define ZI_HIP(call)                                                                                  \
+    do {                                                                                              \
+        hipError_t e_ = (call);                                                                       \
+        if (e_ != hipSuccess) {                                                                       \
+            (void)hipGetLastError(); /* do not leave a sticky error for the caller's next HIP call */ \
+            return ::zi::host::fail(ZI_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+        }                                                                                             \
+    } while (0)
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline zi_status check_dtype(int dt)
+{
+    if (dt != ZI_BF16 && dt != ZI_FP16) return fail(ZI_ERR_INVALID_ARG, "unknown low-precision dtype %d", dt);
+    return ZI_OK;
+}
+
+inline zi_status check_config(const zi_adamw_config* c)
+{
+    if (!c) return fail(ZI_ERR_INVALID_ARG, "cfg is NULL");
+    if (c->step < 1) return fail(ZI_ERR_INVALID_ARG, "step must be >= 1 (got %lld)", (long long)c->step);
+    if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f)) return fail(ZI_ERR_INVALID_ARG, "beta1 must be in [0,1)");
+    if (!(c->beta2 >= 0.0f && c->beta2 < 1.0f)) return fail(ZI_ERR_INVALID_ARG, "beta2 must be in [0,1)");
+    if (!(c->eps >= 0.0f) || std::isinf(c->eps)) return fail(ZI_ERR_INVALID_ARG, "eps must be finite and >= 0");
+    if (!std::isfinite(c->lr)) return fail(ZI_ERR_INVALID_ARG, "lr must be finite");
+    if (!std::isfinite(c->weight_decay)) return fail(ZI_ERR_INVALID_ARG, "weight_decay must be finite");
+    if (!(c->loss_scale > 0.0f) || std::isinf(c->loss_scale))
+        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    if (std::isnan(c->max_grad_norm)) return fail(ZI_ERR_INVALID_ARG, "max_grad_norm is NaN");
+    if (c->mode != ZI_MODE_ADAMW && c->mode != ZI_MODE_ADAM_L2)
+        return fail(ZI_ERR_INVALID_ARG, "unknown mode %d", c->mode);
+    return ZI_OK;
+}
+
+// Tensor list of a step: pointers present and aligned to their element size.
+inline zi_status check_step_tensors(const zi_tensor* t, int32_t n)
+{
+    if (n < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    for (int32_t i = 0; i < n; ++i) {
+        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+        if (t[i].numel == 0) continue;
+        if (!t[i].p || !t[i].m || !t[i].v || !t[i].g)
+            return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v and g must not be NULL", i);
+        if (!aligned(t[i].p, 4) || !aligned(t[i].m, 4) || !aligned(t[i].v, 4))
+            return fail(ZI_ERR_ALIGNMENT, "tensor %d: p, m, v must be 4-byte aligned", i);
+        if (!aligned(t[i].g, 2) || !aligned(t[i].p_lp, 2))
+            return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
+        if (t[i].p == t[i].m || t[i].p == t[i].v || t[i].m == t[i].v || t[i].g == t[i].p_lp)
+            return fail(ZI_ERR_INVALID_ARG, "tensor %d: arrays must not alias each other", i);
+    }
+    return ZI_OK;
+}
+
+// Per-step constants, in double, each rounded once to fp32.
+inline zi::StepConsts make_consts(const zi_adamw_config& c)
+{
+    zi::StepConsts k{};
+    const double b1 = (double)c.beta1, b2 = (double)c.beta2;
+    const double bc1 = 1.0 - std::pow(b1, (double)c.step);
+    const double bc2 = 1.0 - std::pow(b2, (double)c.step);
+    k.beta1 = c.beta1;
+    k.beta2 = c.beta2;
+    k.omb1 = (float)(1.0 - b1);
+    k.omb2 = (float)(1.0 - b2);
+    k.eps = c.eps;
+    k.step_size = (float)((double)c.lr / bc1);
+    k.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+    k.decay = c.mode == ZI_MODE_ADAMW ? (float)((double)c.lr * (double)c.weight_decay) : 0.0f;
+    k.weight_decay = c.weight_decay;
+    k.loss_scale = c.loss_scale;
+    k.max_grad_norm = c.max_grad_norm;
+    k.host_gscale = (float)(1.0 / (double)c.loss_scale);
+    return k;
+}
+
+// Number of leading elements (0..3) before the index at which the fp32 arrays are 16-byte aligned
+// and the 2-byte arrays 8-byte aligned, or -1 if the arrays have no common such index (then only
+// the element-wise kernel applies).
+inline int common_head(const void* p, const void* m, const void* v, const void* g, const void* p_lp)
+{
+    const int h = (int)((4 - (reinterpret_cast<uintptr_t>(g) / 2) % 4) % 4);
+    if (p_lp && (int)((4 - (reinterpret_cast<uintptr_t>(p_lp) / 2) % 4) % 4) != h) return -1;
+    const void* f[3] = {p, m, v};
+    for (const void* x : f)
+        if ((int)((4 - (reinterpret_cast<uintptr_t>(x) / 4) % 4) % 4) != h) return -1;
+    return h;
+}
+
+// Issues the fused step over a list of device-resident segments.
+struct StepIssuer {
+    zi::StepArgs args{};
+    uint32_t tiles = 0;
+    int dt;
+    bool l2;
+    hipStream_t stream;
+    int64_t launches = 0;
+
+    StepIssuer(const zi::StepConsts& c, const zi_norm_result* d_norm, int dt_, bool l2_, hipStream_t s)
+        : dt(dt_), l2(l2_), stream(s)
+    {
+        args.c = c;
+        args.d_norm = d_norm;
+        args.n_desc = 0;
+    }
+
+    hipError_t flush()
+    {
+        hipError_t e = hipSuccess;
+        if (args.n_desc > 0) {
+            e = zi::launch_step_wide(args, tiles, dt, l2, stream);
+            ++launches;
+        }
+        args.n_desc = 0;
+        tiles = 0;
+        return e;
+    }
+
+    hipError_t add(float* p, float* m, float* v, const uint16_t* g, uint16_t* p_lp, int64_t numel)
+    {
+        if (numel <= 0) return hipSuccess;
+        zi::StepDesc d{};
+        d.p = p; d.m = m; d.v = v; d.g = g; d.p_lp = p_lp; d.numel = numel;
+        const int h = common_head(p, m, v, g, p_lp);
+        if (h < 0) {
+            d.head = 0;
+            d.first_tile = 0;
+            ++launches;
+            return zi::launch_step_elementwise(d, args.c, args.d_norm, dt, l2, stream);
+        }
+        d.head = (int32_t)(h < numel ? h : numel);
+        const int64_t nquad = (numel - d.head) / zi::kQuad;
+        int64_t nt = (nquad + zi::kStepTileQuads - 1) / zi::kStepTileQuads;
+        if (nt < 1) nt = 1;                       // the first tile also owns the unaligned ends
+        if (nt > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (args.n_desc == zi::kMaxStepDesc || (uint64_t)tiles + (uint64_t)nt > 0x7FFFFFFFull) {
+            hipError_t e = flush();
+            if (e != hipSuccess) return e;
+        }
+        d.first_tile = tiles;
+        args.t[args.n_desc++] = d;
+        tiles += (uint32_t)nt;
+        return hipSuccess;
+    }
+};
+
+inline zi_status check_norm_args(const zi_tensor* t, int32_t n_tensors, int dt, float loss_scale, zi_norm_result* d_out,
+                          void* d_workspace, size_t workspace_bytes)
+{
+    if (zi_status st = check_dtype(dt)) return st;
+    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
+    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
+        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    if (!d_out) return fail(ZI_ERR_INVALID_ARG, "d_out is NULL");
+    if (!aligned(d_out, 8)) return fail(ZI_ERR_ALIGNMENT, "d_out must be 8-byte aligned");
+    if (!d_workspace) return fail(ZI_ERR_INVALID_ARG, "d_workspace is NULL");
+    if (!aligned(d_workspace, 16)) return fail(ZI_ERR_ALIGNMENT, "d_workspace must be 16-byte aligned");
+    if (workspace_bytes < (size_t)zi::kMaxPartials * sizeof(zi::NormPartial))
+        return fail(ZI_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes,
+                    (size_t)zi::kMaxPartials * sizeof(zi::NormPartial));
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+        if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
+        if (!aligned(t[i].g, 2)) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
+    }
+
+    return ZI_OK;
+}
+
+// Issues the gradient reduction over a list of device-resident gradient arrays: partial-sum launches
+// of up to kMaxNormDesc tensors, and a finalize pass whenever the workspace's partial slots run out
+// and at finish().  After the first finalize the later ones add to the result already in d_out.
+struct NormIssuer {
+    // A workgroup covers at least four tile iterations of its tensor; at most kBlocksPerTensor
+    // workgroups walk one tensor, so the partial count stays small whatever the size.
+    static constexpr int64_t kMinElemsPerBlock = 4 * zi::kNormTileElems;
+    static constexpr int64_t kBlocksPerTensor = 4096;
+
+    zi::NormArgs a{};
+    uint32_t blocks = 0;       // blocks of the launch being assembled
+    uint32_t used = 0;         // partials written since the last finalize
+    int finalized = 0;
+    int dt;
+    float loss_scale;
+    zi_norm_result* d_out;
+    hipStream_t s;
+
+    NormIssuer(zi::NormPartial* partials, int dt_, float ls, zi_norm_result* out, hipStream_t st)
+        : dt(dt_), loss_scale(ls), d_out(out), s(st)
+    {
+        a.partials = partials;
+        a.partial_base = 0;
+        a.n_desc = 0;
+    }
+    hipError_t flush_launch()
+    {
+        hipError_t e = hipSuccess;
+        if (a.n_desc > 0) e = zi::launch_norm_partials(a, blocks, dt, s);
+        used += blocks;
+        a.partial_base = used;
+        a.n_desc = 0;
+        blocks = 0;
+        return e;
+    }
+    hipError_t flush_partials()
+    {
+        hipError_t e = zi::launch_norm_finalize(a.partials, used, loss_scale, finalized, d_out, s);
+        finalized = 1;
+        used = 0;
+        a.partial_base = 0;
+        return e;
+    }
+    hipError_t add(const uint16_t* g, int64_t n)
+    {
+        if (n <= 0) return hipSuccess;
+        int64_t nb = (n + kMinElemsPerBlock - 1) / kMinElemsPerBlock;
+        if (nb > kBlocksPerTensor) nb = kBlocksPerTensor;
+        hipError_t e = hipSuccess;
+        if (a.n_desc == zi::kMaxNormDesc && (e = flush_launch()) != hipSuccess) return e;
+        if ((uint64_t)used + blocks + (uint64_t)nb > zi::kMaxPartials) {
+            if ((e = flush_launch()) != hipSuccess) return e;
+            if ((e = flush_partials()) != hipSuccess) return e;
+        }
+        zi::NormDesc d{};
+        d.g = g;
+        d.numel = n;
+        const int h = (int)((8 - (reinterpret_cast<uintptr_t>(g) / 2) % 8) % 8);
+        d.head = (int32_t)(h < n ? h : n);
+        d.first_block = blocks;
+        d.n_blocks = (uint32_t)nb;
+        a.t[a.n_desc++] = d;
+        blocks += (uint32_t)nb;
+        return hipSuccess;
+    }
+    hipError_t finish()
+    {
+        hipError_t e = flush_launch();
+        if (e != hipSuccess) return e;
+        return flush_partials();
+    }
+};
+
+
+// Chunk plan of the streamed step (zi_plan.hip).
+constexpr int64_t kPackAlign = 1024; // packed segments start on 4096-byte boundaries of the slot arrays (direct file I/O)
+constexpr int64_t kPhasePad = 8;     // room for lead-in elements that keep alignment phases equal
+
+struct Segment {
+    int32_t tensor;
+    int64_t elem_offset, count, slot_use, slot_offset;
+};
+
+void plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems, std::vector<Segment>& out,
+                 int64_t& n_uses);
+
+}  // namespace host
+}  // namespace zi
