@@ -214,6 +214,21 @@ def streamed(args, torch, zi, zs):
             off_step.append(zi.zi_engine_last_stats(eng).seconds)
         del hg, hlp
 
+        # The paper's own placement: the step on the host CPUs over host-resident state (no GPU involved);
+        # beside it the link would carry only 2 B/element of gradients down and 2 B/element of copy up.
+        log("streamed: host-CPU step on the same slice, for the crossover")
+        hg2 = hp.numpy().view("uint16")[:n].copy()         # any 16-bit patterns of plausible magnitude
+        hg2[:] = 0x3A00
+        hlp2 = torch.zeros(n, dtype=torch.int16).numpy().view("uint16")
+        tl_cpu = zi.make_tensors([(hp, hm, hv, hg2, hlp2, n)])
+        ncores = min(os.cpu_count() or 1, 16)
+        cpu_step = []
+        for _ in range(3):
+            t0c = time.perf_counter()
+            zi.zi_host_adamw_step(tl_cpu, w["lp_dtype"], cfg, None, ncores)
+            cpu_step.append(time.perf_counter() - t0c)
+        del hg2, hlp2
+
         # State in ordinary (not page-locked) host memory, through a 6-slot pinned ring.
         log("streamed: ordinary host memory through the pinned ring")
         op, om, ov = hp.numpy().copy(), hm.numpy().copy(), hv.numpy().copy()
@@ -242,6 +257,10 @@ def streamed(args, torch, zi, zs):
             step_frac_of_bidir_peak=round(14 * n / min(off_step) / 1e9 / peaks["bidir"], 4),
             norm_GBps=round(2 * n / min(off_norm) / 1e9, 2),
             norm_frac_of_h2d_peak=round(2 * n / min(off_norm) / 1e9 / peaks["h2d"], 4)),
+        host_cpu_step=dict(
+            what=f"zi_host_adamw_step on the same slice, {ncores} threads (the paper's CPU-side placement); "
+                 "reported for the crossover, never used as a fallback",
+            params_per_s=n / min(cpu_step), host_memory_GBps=round(28 * n / min(cpu_step) / 1e9, 1)),
         ordinary_memory_ring=dict(
             what="p, m, v in ordinary host memory, 6-slot pinned ring, 7 copy threads per direction",
             GBps_per_direction=round(12 * n / min(ring) / 1e9, 2),

@@ -313,6 +313,25 @@ zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_
                          int64_t cap, int64_t* n_segments_out, int64_t* n_slot_uses_out);
 
 /*
+ * The step on the host CPUs, for state, gradients and copy that all live in HOST memory (any host
+ * memory).  This is the paper's own placement of the offloaded step (Section 5.2.2: with optimizer
+ * states in CPU memory the step uses the CPUs' aggregate compute and memory bandwidth; only 2 bytes
+ * of gradient per element come down the link and 2 bytes of low-precision parameter go up).  These
+ * two calls are chosen explicitly by the caller: no GPU entry point ever falls back to them, and
+ * they touch no GPU.  Same arithmetic in the same order as the GPU kernels (AVX2 / FMA / F16C
+ * vector code, n_threads threads, blocks of 2^18 elements); ZI_ERR_UNSUPPORTED on a CPU without
+ * those instructions.  Blocking.
+ * zi_host_grad_norm: as zi_grad_norm, result written to HOST memory h_out; block partials are
+ * added in block order, so the result does not depend on n_threads.
+ * zi_host_adamw_step: as zi_adamw_step; h_norm is a HOST result or NULL; returns
+ * ZI_SKIPPED_OVERFLOW (nothing touched) if h_norm->found_inf is set.
+ */
+zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
+                            zi_norm_result* h_out, int32_t n_threads);
+zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, const zi_adamw_config* cfg,
+                             const zi_norm_result* h_norm, int32_t n_threads);
+
+/*
  * HBM stream probe (a measurement aid): one launch with the fused step's access shape and no
  * arithmetic, over `bytes` (positive multiple of 16) of 16-byte aligned device memory.
  * mode 0 = read d_a; mode 1 = copy d_a to d_b (non-overlapping); mode 2 = update d_a in place

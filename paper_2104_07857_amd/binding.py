@@ -33,6 +33,7 @@ EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
     "zi_grad_norm_streamed", "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
+    "zi_host_grad_norm", "zi_host_adamw_step",
 ]
 
 
@@ -123,6 +124,12 @@ def lib() -> ctypes.CDLL:
         L.zi_plan_chunks.restype = ctypes.c_int
         L.zi_plan_chunks.argtypes = [ctypes.POINTER(i64), i32, i64, ctypes.POINTER(zi_chunk_segment), i64,
                                      ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.zi_host_grad_norm.restype = ctypes.c_int
+        L.zi_host_grad_norm.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int, ctypes.c_float,
+                                        ctypes.POINTER(zi_norm_result), i32]
+        L.zi_host_adamw_step.restype = ctypes.c_int
+        L.zi_host_adamw_step.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
+                                         ctypes.POINTER(zi_adamw_config), ctypes.POINTER(zi_norm_result), i32]
         L.zi_hbm_probe.restype = ctypes.c_int
         L.zi_hbm_probe.argtypes = [vp, vp, sz, i32, vp]
         L.zi_pinned_alloc.restype = ctypes.c_int
@@ -289,6 +296,21 @@ def zi_plan_chunks(numel: Sequence[int], chunk_elems: int):
     out = (zi_chunk_segment * max(nseg.value, 1))()
     _check(lib().zi_plan_chunks(arr, n, int(chunk_elems), out, nseg.value, ctypes.byref(nseg), ctypes.byref(nuse)))
     return [out[i] for i in range(nseg.value)], nuse.value
+
+
+def zi_host_grad_norm(tensors, dt: int, loss_scale: float, n_threads: int = 1) -> zi_norm_result:
+    """Host-CPU reduction over host-resident gradients; returns the (host) result struct."""
+    arr, n = _as_tensor_array(tensors)
+    out = zi_norm_result()
+    _check(lib().zi_host_grad_norm(arr, n, int(dt), float(loss_scale), ctypes.byref(out), int(n_threads)))
+    return out
+
+
+def zi_host_adamw_step(tensors, dt: int, cfg: zi_adamw_config, h_norm: Optional[zi_norm_result] = None,
+                       n_threads: int = 1) -> int:
+    arr, n = _as_tensor_array(tensors)
+    return _check(lib().zi_host_adamw_step(arr, n, int(dt), ctypes.byref(cfg) if cfg is not None else None,
+                                           ctypes.byref(h_norm) if h_norm is not None else None, int(n_threads)))
 
 
 def zi_hbm_probe(d_a, d_b, nbytes: int, mode: int, stream=None) -> int:

@@ -37,12 +37,24 @@ def needs_build() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+# The host-CPU step is plain C++ with AVX2 / FMA / F16C intrinsics, built by the host compiler.
+HOST_SOURCES = ["zi_cpu_step.cpp"]
+HOST_FLAGS = ["-O3", "-std=c++17", "-fPIC", "-mavx2", "-mfma", "-mf16c", "-ffp-contract=off", "-fno-fast-math",
+              "-Wall", "-Wextra", "-pthread"]
+
+
 def build(force: bool = True, extra_flags=(), out: str | None = None) -> str:
     out = out or LIB_PATH
     if not force and out == LIB_PATH and not needs_build():
         return out
+    objs = []
+    for src in HOST_SOURCES:
+        obj = os.path.join(HERE, "_" + os.path.splitext(src)[0] + ".o")
+        subprocess.run(["g++", *HOST_FLAGS, "-I", os.path.join(ROOT, "include"), "-c", os.path.join(CSRC, src),
+                        "-o", obj], check=True)
+        objs.append(obj)
     cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", out, *[os.path.join(CSRC, s) for s in SOURCES]]
+           "-o", out, *[os.path.join(CSRC, s) for s in SOURCES], *["-Wl," + o for o in objs], "-pthread"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops' is not a recognized feature"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
