@@ -62,6 +62,8 @@
  *     offset by the same number of elements, modulo 4).  Any other placement
  *     takes a slower element-wise path with identical results.
  *   - numel == 0 and n_tensors == 0 are valid and do nothing.
+ *   - Threads: calls that do not share buffers or an engine may run concurrently from different
+ *     threads.  An engine serves one call at a time.  zi_last_error() is per thread.
  *   - The library is gfx950-only and has no CPU fallback: without a usable HIP
  *     device every compute call returns ZI_ERR_HIP.
  */

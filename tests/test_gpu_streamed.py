@@ -103,6 +103,17 @@ def test_ragged_list_with_packing_and_global_clip(engine, g_offset):
     progress(f"streamed ragged (g offset {g_offset}): {uses} slot uses, {st.n_kernels} launches; last {rep}")
 
 
+def test_streamed_without_low_precision_copy(engine):
+    n = 3 * 16384 + 99
+    w = zi_synth.workload("c2")
+    p, m, v, g = gen_numpy(zi_synth.StateSpec(8, zi.ZI_BF16), n)
+    pe, me, ve = p.copy(), m.copy(), v.copy()
+    oracle.adamw(pe, me, ve, g, None, zi.ZI_BF16, oracle_cfg(w))
+    pp, pm, pv = _pinned(p), _pinned(m), _pinned(v)
+    assert zi.zi_adamw_step_streamed(engine, [(pp, pm, pv, to_dev(g), None, n)], zi.ZI_BF16, zi_cfg(w)) == zi.ZI_OK
+    compare_state((pe, me, ve, None), (pp.numpy(), pm.numpy(), pv.numpy(), None), zi.ZI_BF16)
+
+
 def test_overflow_skips_without_moving_state(engine):
     w = zi_synth.workload("c3")
     n = 3 * 16384 + 5
