@@ -180,6 +180,16 @@ def test_c2_streamed_8e9_from_pinned_host():
         assert stats.n_slot_uses == (n + chunk - 1) // chunk and stats.bytes_h2d == 12 * n == stats.bytes_d2h
         assert n != 8_000_000_000 or stats.n_slot_uses == 477
         progress(f"c2: streamed in {stats.seconds:.2f} s = {12 * n / stats.seconds / 1e9:.1f} GB/s per direction")
+        # Reads, the update and writes of different chunks overlap: were they serialised, the rate per
+        # direction could not exceed half of the slower one-way rate.
+        nbytes = 1 << 30
+        scratch = PinnedF32(nbytes // 4)
+        try:
+            one_way = min(nbytes / zi.zi_engine_link_probe(eng, hp.ptr, scratch.ptr, nbytes, mode, 1)
+                          for mode in (0, 1))
+        finally:
+            scratch.free()
+        assert 12 * n / stats.seconds > 0.6 * one_way, "the pipeline does not overlap its two directions"
         tail0 = (n // chunk) * chunk
         ranges = sample_ranges(n, WIDTH, extra_points=(chunk, 2 * chunk, 3 * chunk, 100 * chunk, 1 << 32, tail0),
                                count=8, seed=2)

@@ -103,6 +103,30 @@ def test_ragged_list_with_packing_and_global_clip(engine, g_offset):
     progress(f"streamed ragged (g offset {g_offset}): {uses} slot uses, {st.n_kernels} launches; last {rep}")
 
 
+@pytest.mark.parametrize("chunk_bytes,slots", [(4096, 2), (4096, 8), (1 << 20, 3), (1 << 22, 4)])
+def test_chunk_size_and_slot_count_do_not_change_a_bit(chunk_bytes, slots):
+    """Chunked processing equals unchunked processing for any chunk size, including chunks larger than
+    the whole state, and any number of slots."""
+    n = 300_007
+    w = zi_synth.workload("c2")
+    p, m, v, g = gen_numpy(zi_synth.StateSpec(55, zi.ZI_BF16), n)
+    dp, dm, dv, dg = (to_dev(a) for a in (p, m, v, g))
+    rlp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    zi.zi_adamw_step([(dp, dm, dv, dg, rlp, n)], zi.ZI_BF16, zi_cfg(w))
+    pp, pm, pv = _pinned(p), _pinned(m), _pinned(v)
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    eng = zi.zi_engine_create(0, chunk_bytes, slots)
+    try:
+        assert zi.zi_adamw_step_streamed(eng, [(pp, pm, pv, dg, lp, n)], zi.ZI_BF16, zi_cfg(w)) == zi.ZI_OK
+        assert zi.zi_engine_last_stats(eng).n_slot_uses == -(-n // (chunk_bytes // 4))
+    finally:
+        zi.zi_engine_destroy(eng)
+    torch.cuda.synchronize()
+    for a, b in ((pp, dp), (pm, dm), (pv, dv)):
+        assert np.array_equal(a.numpy().view(np.uint32), to_np(b).view(np.uint32))
+    assert torch.equal(lp, rlp)
+
+
 def test_streamed_without_low_precision_copy(engine):
     n = 3 * 16384 + 99
     w = zi_synth.workload("c2")
