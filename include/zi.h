@@ -266,6 +266,9 @@ zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
  * Engine options.
  * ZI_OPT_SKIP_KERNEL = 1 runs the identical copy pipeline without launching the
  * update (a measurement aid: the time of the pipeline with the update removed).
+ * ZI_OPT_MAX_INFLIGHT = k: before issuing a slot use the host waits for the use k positions back
+ * to finish.  The default 2 keeps copy-in and copy-out in lockstep, which measured fastest and
+ * steadiest; with n_slots = 3 the third slot then only decouples the host's issue from completion.
  * ZI_OPT_HOST_RING_SLOTS = n gives the engine a ring of n pinned host slots
  * (each 3 arrays of the chunk size) and two small CPU thread pools.  With it,
  * zi_adamw_step_streamed also accepts p, m, v in ORDINARY (pageable) host
@@ -278,7 +281,8 @@ zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
 typedef enum {
     ZI_OPT_SKIP_KERNEL = 0,
     ZI_OPT_HOST_RING_SLOTS = 1,    /* 0 = none (default); 2..16: allocate a pinned ring of that many slots */
-    ZI_OPT_HOST_COPY_THREADS = 2   /* 1..64 CPU threads per direction for the ring (default 6) */
+    ZI_OPT_HOST_COPY_THREADS = 2,  /* 1..64 CPU threads per direction for the ring (default 6) */
+    ZI_OPT_MAX_INFLIGHT = 3        /* 1..n_slots slot uses the host keeps in flight (default 2) */
 } zi_engine_option;
 zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t value);
 

@@ -28,6 +28,7 @@ ZI_MODE_ADAM_L2 = 1
 ZI_OPT_SKIP_KERNEL = 0
 ZI_OPT_HOST_RING_SLOTS = 1
 ZI_OPT_HOST_COPY_THREADS = 2
+ZI_OPT_MAX_INFLIGHT = 3
 
 EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",

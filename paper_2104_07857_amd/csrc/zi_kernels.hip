@@ -197,9 +197,20 @@ __global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs
     const u32x2* __restrict__ g2 = reinterpret_cast<const u32x2*>(T.g + head);
     u32x2* __restrict__ lp2 = T.p_lp ? reinterpret_cast<u32x2*>(T.p_lp + head) : nullptr;
 
-    const int64_t q0 = (int64_t)tile * kStepTileQuads + threadIdx.x;
+    // XCD-aware renumbering (a bijection on the complete runs of 8 * kStepXcdRun tiles; the few
+    // tiles after the last complete run keep their numbers).
+    int64_t ti = tile;
+    {
+        constexpr int64_t run = kXcds * kStepXcdRun;
+        const int64_t ntiles = (nquad + kStepTileQuads - 1) / kStepTileQuads;
+        if (ti < ntiles / run * run) {
+            const int64_t r = ti % run;
+            ti = ti - r + (r % kXcds) * kStepXcdRun + r / kXcds;
+        }
+    }
+    const int64_t q0 = ti * kStepTileQuads + threadIdx.x;
 
-    if ((int64_t)(tile + 1) * kStepTileQuads <= nquad) {
+    if ((ti + 1) * kStepTileQuads <= nquad) {
         // full tile: every load is issued before the first result is needed
         f32x4 p[kStepUnroll], m[kStepUnroll], v[kStepUnroll];
         u32x2 g[kStepUnroll];
