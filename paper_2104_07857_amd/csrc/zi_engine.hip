@@ -886,19 +886,35 @@ extern "C" zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, vo
     ZI_HIP(hipStreamSynchronize(e->s_d2h));
 
     // Host-to-device pieces land in the p arrays of the slots, device-to-host pieces leave from
-    // the m arrays, so the two directions never touch the same staging bytes.
+    // the m arrays, so the two directions never touch the same staging bytes.  In the two-way mode
+    // the host keeps the same number of pieces in flight as the streamed step does (a deep queue
+    // lets one direction run ahead and measures a lower two-way rate).
+    const int depth = e->max_inflight < e->n_slots ? e->max_inflight : e->n_slots;
     const auto t0 = std::chrono::steady_clock::now();
     for (int r = 0; r < repeats; ++r) {
-        int piece = 0;
+        int64_t piece = 0;
         for (size_t off = 0; off < bytes; off += e->chunk_bytes, ++piece) {
             const size_t nb = bytes - off < e->chunk_bytes ? bytes - off : e->chunk_bytes;
-            const int slot = piece % e->n_slots;
+            const int slot = (int)(piece % e->n_slots);
+            if (mode == 2 && piece >= depth) {
+                const int old_slot = (int)((piece - depth) % e->n_slots);
+                ZI_HIP(hipEventSynchronize(e->ev_h2d[old_slot]));
+                ZI_HIP(hipEventSynchronize(e->ev_d2h[old_slot]));
+            }
             if (mode == 0 || mode == 2)
                 ZI_HIP(hipMemcpyAsync(e->slot_array(slot, 0), (const char*)host_src + off, nb,
                                       hipMemcpyHostToDevice, e->s_h2d));
             if (mode == 1 || mode == 2)
                 ZI_HIP(hipMemcpyAsync((char*)host_dst + off, e->slot_array(slot, 1), nb, hipMemcpyDeviceToHost,
                                       e->s_d2h));
+            if (mode == 2) {
+                ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
+                ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
+            }
+        }
+        if (mode == 2) {     // the next repeat starts with an empty pipeline
+            ZI_HIP(hipStreamSynchronize(e->s_h2d));
+            ZI_HIP(hipStreamSynchronize(e->s_d2h));
         }
     }
     ZI_HIP(hipStreamSynchronize(e->s_h2d));
