@@ -39,6 +39,7 @@
 static inline uint32_t f32_bits(float x) { uint32_t b; memcpy(&b, &x, 4); return b; }
 static inline float bits_f32(uint32_t b) { float x; memcpy(&x, &b, 4); return x; }
 
+/* Low-precision -> fp32, exact (Section 3: parameters and gradients are kept in 16-bit formats). */
 float zio_bf16_to_f32(uint16_t h)
 {
     return bits_f32((uint32_t)h << 16);
@@ -57,7 +58,9 @@ float zio_f16_to_f32(uint16_t h)
     return bits_f32(sign | ((e + 112u) << 23) | (f << 13));
 }
 
-/* fp32 -> bf16, round to nearest, ties to even; NaN stays NaN (quieted). */
+/* fp32 -> bf16, round to nearest, ties to even; NaN stays NaN (quieted).  The low-precision copy of
+ * the updated fp32 parameter (Section 3; Table 1's "fp16 param" placement); the paper names no rounding
+ * mode, IEEE-754 round-to-nearest-even is the reading taken. */
 uint16_t zio_f32_to_bf16(float x)
 {
     uint32_t b = f32_bits(x);
@@ -66,7 +69,7 @@ uint16_t zio_f32_to_bf16(float x)
     return (uint16_t)(b >> 16);
 }
 
-/* fp32 -> fp16, round to nearest, ties to even; subnormals kept; overflow -> inf. */
+/* fp32 -> fp16, round to nearest, ties to even; subnormals kept; overflow -> inf (same passage). */
 uint16_t zio_f32_to_f16(float x)
 {
     const uint32_t b = f32_bits(x);
@@ -113,6 +116,8 @@ void zio_widen_array(const uint16_t* x, float* out, int64_t n, int dtype)
 
 /* ------------------------------------------------ gradient norm and overflow */
 
+/* Global gradient norm and overflow flag: not written down in the paper (Section 2 only cites
+ * mixed-precision training); the standard dynamic-loss-scaling rule is taken. */
 void zio_sumsq_init(zio_sumsq_state* st)
 {
     st->sum = 0.0;
