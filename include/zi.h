@@ -144,6 +144,17 @@ zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, fl
                        zi_norm_result* d_out, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Hook for a sharded run (Section 2, "ZeRO": every data-parallel process owns a slice of each
+ * parameter and steps only that slice; the clip factor needs the norm over ALL slices).  Each rank
+ * calls zi_grad_norm on its slice; the caller then combines the results across ranks, in place in
+ * device memory, with whatever collective it uses (sumsq: sum, found_inf: max, 12 bytes in all);
+ * zi_norm_refresh recomputes d_result->norm = sqrt(sumsq) / loss_scale from the combined sum, after
+ * which zi_adamw_step proceeds as on one GPU.  The library itself issues no collective.
+ * Asynchronous on hip_stream.
+ */
+zi_status zi_norm_refresh(zi_norm_result* d_result, float loss_scale, void* hip_stream);
+
+/*
  * Fused AdamW step over HBM-resident state (Sections 3 and 4.1; equations in
  * the header comment).  All arrays of every tensor are device memory; p, m, v
  * are updated in place and p_lp (if not NULL) receives the low-precision copy.

@@ -34,7 +34,7 @@ EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
     "zi_grad_norm_streamed", "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
-    "zi_host_grad_norm", "zi_host_adamw_step",
+    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh",
 ]
 
 
@@ -131,6 +131,8 @@ def lib() -> ctypes.CDLL:
         L.zi_host_adamw_step.restype = ctypes.c_int
         L.zi_host_adamw_step.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
                                          ctypes.POINTER(zi_adamw_config), ctypes.POINTER(zi_norm_result), i32]
+        L.zi_norm_refresh.restype = ctypes.c_int
+        L.zi_norm_refresh.argtypes = [vp, ctypes.c_float, vp]
         L.zi_hbm_probe.restype = ctypes.c_int
         L.zi_hbm_probe.argtypes = [vp, vp, sz, i32, vp]
         L.zi_pinned_alloc.restype = ctypes.c_int
@@ -312,6 +314,10 @@ def zi_host_adamw_step(tensors, dt: int, cfg: zi_adamw_config, h_norm: Optional[
     arr, n = _as_tensor_array(tensors)
     return _check(lib().zi_host_adamw_step(arr, n, int(dt), ctypes.byref(cfg) if cfg is not None else None,
                                            ctypes.byref(h_norm) if h_norm is not None else None, int(n_threads)))
+
+
+def zi_norm_refresh(d_result, loss_scale: float, stream=None) -> int:
+    return _check(lib().zi_norm_refresh(_addr(d_result), float(loss_scale), _stream(stream)))
 
 
 def zi_hbm_probe(d_a, d_b, nbytes: int, mode: int, stream=None) -> int:

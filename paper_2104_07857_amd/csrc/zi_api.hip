@@ -53,6 +53,16 @@ extern "C" zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_d
     return ZI_OK;
 }
 
+extern "C" zi_status zi_norm_refresh(zi_norm_result* d_result, float loss_scale, void* hip_stream)
+{
+    if (!d_result) return fail(ZI_ERR_INVALID_ARG, "d_result is NULL");
+    if (!aligned(d_result, 8)) return fail(ZI_ERR_ALIGNMENT, "d_result must be 8-byte aligned");
+    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
+        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    ZI_HIP(zi::launch_norm_refresh(d_result, loss_scale, (hipStream_t)hip_stream));
+    return ZI_OK;
+}
+
 // =============================================================================== resident step
 
 extern "C" zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,

@@ -100,6 +100,7 @@ hipError_t launch_norm_partials(const NormArgs& a, uint32_t n_blocks, int dt, hi
 hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, float loss_scale, int accumulate,
                                 zi_norm_result* d_out, hipStream_t s);
 
+hipError_t launch_norm_refresh(zi_norm_result* d_result, float loss_scale, hipStream_t s);
 hipError_t launch_hbm_probe(void* a, void* b, int64_t n4, int mode, float* sink, hipStream_t s);
 
 }  // namespace zi

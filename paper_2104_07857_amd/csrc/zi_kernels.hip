@@ -453,6 +453,22 @@ __global__ __launch_bounds__(kFinalThreads) void norm_finalize_kernel(const Norm
     }
 }
 
+// After the sum of squares and the flag have been combined across ranks (sum and max), the norm
+// field is recomputed from the combined sum.
+__global__ void norm_refresh_kernel(zi_norm_result* r, float loss_scale)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        r->norm = __builtin_sqrt(r->sumsq) / (double)loss_scale;
+        r->found_inf = r->found_inf ? 1u : 0u;
+    }
+}
+
+hipError_t launch_norm_refresh(zi_norm_result* d_result, float loss_scale, hipStream_t s)
+{
+    hipLaunchKernelGGL(norm_refresh_kernel, dim3(1), dim3(64), 0, s, d_result, loss_scale);
+    return hipGetLastError();
+}
+
 hipError_t launch_norm_partials(const NormArgs& a, uint32_t n_blocks, int dt, hipStream_t s)
 {
     if (n_blocks == 0) return hipSuccess;

@@ -119,3 +119,42 @@ def test_hbm_probe_modes_do_what_they_say():
     zi.zi_hbm_probe(a, None, 4 * n, 2)
     torch.cuda.synchronize()
     assert torch.equal(a, ref + 1.0)
+
+
+def test_two_slices_combined_like_two_ranks_give_the_global_clip():
+    """The sharded recipe on one GPU: each 'rank' reduces its slice, the 12 bytes are combined (sum, max) in
+    device memory, zi_norm_refresh recomputes the norm, and each slice is stepped with the combined result:
+    identical to stepping the whole tensor with its own norm."""
+    from gpu_util import gen_numpy, zi_cfg
+    w = zi_synth.workload("c4")
+    dt = zi.ZI_BF16
+    n, k = 300_001, 123_457
+    p, m, v, g = gen_numpy(zi_synth.StateSpec(314, dt, g_std=2e-3), n)
+    cfg = zi_cfg(w)
+    whole = [to_dev(a) for a in (p, m, v, g)] + [torch.zeros(n, dtype=torch.int16, device="cuda:0")]
+    nb = NormBuffers()
+    zi.zi_grad_norm([tuple(whole) + (n,)], dt, 1.0, nb.out, nb.ws)
+    zi.zi_adamw_step([tuple(whole) + (n,)], dt, cfg, nb.out)
+    parts = [to_dev(a) for a in (p, m, v, g)] + [torch.zeros(n, dtype=torch.int16, device="cuda:0")]
+    r0, r1 = NormBuffers(), NormBuffers()
+    s0 = tuple(x[:k] for x in parts) + (k,)
+    s1 = tuple(x[k:] for x in parts) + (n - k,)
+    zi.zi_grad_norm([s0], dt, 1.0, r0.out, r0.ws)
+    zi.zi_grad_norm([s1], dt, 1.0, r1.out, r1.ws)
+    # the "all-reduce": sum of sumsq, max of the flag word, written back to both ranks' results
+    total = r0.out[0] + r1.out[0]
+    flag = torch.maximum(r0.out[2:3].view(torch.int64), r1.out[2:3].view(torch.int64))
+    for r in (r0, r1):
+        r.out[0] = total
+        r.out[2:3].view(torch.int64).copy_(flag)
+        zi.zi_norm_refresh(r.out, 1.0)
+    zi.zi_adamw_step([s0], dt, cfg, r0.out)
+    zi.zi_adamw_step([s1], dt, cfg, r1.out)
+    torch.cuda.synchronize()
+    assert abs(r0.read()[1] - nb.read()[1]) <= 1e-12 * nb.read()[1] and r0.read()[2] == 0
+    for a, b in zip(whole, parts):
+        assert torch.equal(a, b)
+    with pytest.raises(zi.ZiError):
+        zi.zi_norm_refresh(None, 1.0)
+    with pytest.raises(zi.ZiError):
+        zi.zi_norm_refresh(r0.out, 0.0)
