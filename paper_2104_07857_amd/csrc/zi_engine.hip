@@ -20,50 +20,54 @@ constexpr int kMaxHostSlots = 16;
 // second half stages a host-resident low-precision copy.
 constexpr int kSlotArrays = 4;
 
-
 }  // namespace
 
 struct zi_engine {
-    // Pinned ring for state that lives in ordinary (pageable) host memory: n_hslots slots shaped like
-    // the HBM slots, filled and emptied by two small thread pools.
+    int device = 0;
+    size_t chunk_bytes = 0;            // per state array
+    int64_t chunk_elems = 0;
+    size_t array_bytes = 0;            // chunk_bytes + room for lead-in elements and a rounded-up last block
+    uint32_t magic = 0;
+
+    // HBM staging: n_slots slots of kSlotArrays arrays, three streams, events that order slot reuse.
+    int n_slots = 0;
+    char* staging = nullptr;
+    hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
+    hipEvent_t ev_h2d[8] = {}, ev_k[8] = {}, ev_d2h[8] = {};
+    hipEvent_t ev_in = nullptr, ev_out = nullptr;
+    zi_norm_result* h_norm = nullptr;  // pinned landing place of the norm result
+
+    // Pinned ring for state that is not page-locked (ordinary memory, files): n_hslots slots shaped
+    // like the HBM slots, filled and emptied by two small thread pools.
     int n_hslots = 0;
     char* hring = nullptr;
     hipEvent_t ev_back[kMaxHostSlots] = {};
     int copy_threads = 6;
     CopyPool* pool_in = nullptr;
     CopyPool* pool_out = nullptr;
-    float* hslot_array(int hslot, int which) const
-    {
-        return reinterpret_cast<float*>(hring + ((size_t)hslot * kSlotArrays + which) * array_bytes);
-    }
-    int device = 0;
-    size_t chunk_bytes = 0;
-    int64_t chunk_elems = 0;
-    int n_slots = 0;
-    size_t array_bytes = 0;            // chunk_bytes + room for phase lead-in
-    char* staging = nullptr;           // n_slots * kSlotArrays * array_bytes
-    hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
-    hipEvent_t ev_h2d[8] = {}, ev_k[8] = {}, ev_d2h[8] = {};
-    hipEvent_t ev_in = nullptr, ev_out = nullptr;
-    zi_norm_result* h_norm = nullptr;  // pinned landing place of the norm result
+
+    // options and figures
     int64_t skip_kernel = 0;
     int max_inflight = 2;              // slot uses the host keeps in flight (<= n_slots)
     zi_stream_stats stats{};
-    uint32_t magic = 0;
 
+    float* slot_array(int slot, int which) const
+    {
+        return reinterpret_cast<float*>(staging + ((size_t)slot * kSlotArrays + which) * array_bytes);
+    }
     uint16_t* slot_g(int slot) const { return reinterpret_cast<uint16_t*>(slot_array(slot, 3)); }
     uint16_t* slot_lp(int slot) const
     {
         return reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(slot_array(slot, 3)) + array_bytes / 2);
     }
+    float* hslot_array(int hslot, int which) const
+    {
+        return reinterpret_cast<float*>(hring + ((size_t)hslot * kSlotArrays + which) * array_bytes);
+    }
     uint16_t* hslot_g(int h) const { return reinterpret_cast<uint16_t*>(hslot_array(h, 3)); }
     uint16_t* hslot_lp(int h) const
     {
         return reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(hslot_array(h, 3)) + array_bytes / 2);
-    }
-    float* slot_array(int slot, int which) const
-    {
-        return reinterpret_cast<float*>(staging + ((size_t)slot * kSlotArrays + which) * array_bytes);
     }
 };
 
@@ -278,6 +282,15 @@ int memory_kind(const void* p)
     return -1;
 }
 
+// After a failed call: wait for whatever the engine's streams still hold, keeping the first error.
+void drain_streams(zi_engine* e)
+{
+    (void)hipStreamSynchronize(e->s_h2d);
+    (void)hipStreamSynchronize(e->s_k);
+    (void)hipStreamSynchronize(e->s_d2h);
+    (void)hipGetLastError();
+}
+
 // The chunk pipeline.  `staged` = the state is not page-locked memory and travels through the
 // engine's pinned ring (CPU threads fill and empty the ring slots).
 zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool staged, zi_lp_dtype dt,
@@ -381,7 +394,16 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
     } sync;
     uint64_t staged_bytes = 0;
     std::thread gather_thread, scatter_thread;
-    if (staged) {
+    auto stop_threads = [&] {
+        {
+            std::lock_guard<std::mutex> lk(sync.mu);
+            sync.abort = true;
+        }
+        sync.cv.notify_all();
+        if (gather_thread.joinable()) gather_thread.join();
+        if (scatter_thread.joinable()) scatter_thread.join();
+    };
+    if (staged) try {
         gather_thread = std::thread([&] {
             std::vector<CopyPool::Piece> pieces;
             for (int64_t u = 0; u < n_uses; ++u) {
@@ -440,6 +462,9 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
                 if (err) return;
             }
         });
+    } catch (const std::exception& ex) {
+        stop_threads();
+        return fail(ZI_ERR_NOMEM, "could not start the ring's copy threads: %s", ex.what());
     }
 
     const auto t0 = std::chrono::steady_clock::now();
@@ -560,6 +585,7 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
     };
 
     zi_status st = pipeline();
+    if (st != ZI_OK) drain_streams(e);     // nothing of ours still touches the caller's memory on return
     if (staged) {
         if (st != ZI_OK) {
             std::lock_guard<std::mutex> lk(sync.mu);
@@ -574,7 +600,6 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
     e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return st;
 }
-
 
 }  // namespace
 
@@ -683,7 +708,7 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
         bool abort = false;
     } sync;
     std::thread gather_thread;
-    if (pageable) {
+    if (pageable) try {
         gather_thread = std::thread([&] {
             (void)hipSetDevice(e->device);
             std::vector<CopyPool::Piece> pieces;
@@ -721,6 +746,8 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
                 sync.cv.notify_all();
             }
         });
+    } catch (const std::exception& ex) {
+        return fail(ZI_ERR_NOMEM, "could not start the ring's copy thread: %s", ex.what());
     }
 
     const auto t0 = std::chrono::steady_clock::now();
@@ -773,6 +800,7 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
         return ZI_OK;
     };
     zi_status st = pipeline();
+    if (st != ZI_OK) drain_streams(e);
     if (pageable) {
         if (st != ZI_OK) {
             std::lock_guard<std::mutex> lk(sync.mu);
