@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--cpu-sample", type=int, default=1_300_000_000, help="elements the oracle is timed on")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (scales rocprofv3 byte counters)")
+    ap.add_argument("--file-numel", type=int, default=1 << 28,
+                    help="elements of the file-tier figure (three files of 4 bytes each; 0 = leave it out)")
     ap.add_argument("--streamed-numel", type=int, default=1 << 30,
                     help="elements of the host-resident state used for the streamed measurement")
     return ap.parse_args()
@@ -241,6 +243,9 @@ def streamed(args, torch, zi, zs):
             zi.zi_adamw_step_streamed(eng, tl_ring, w["lp_dtype"], cfg)
             ring.append(zi.zi_engine_last_stats(eng).seconds)
         del op, om, ov
+
+        # State in files on the box's disk (direct I/O), through the same ring: the NVMe-tier figure.
+        file_tier = file_tier_figures(args, zi, eng, spec, g, lp, w, cfg)
     finally:
         zi.zi_engine_destroy(eng)
     t = min(times)
@@ -267,7 +272,58 @@ def streamed(args, torch, zi, zs):
         ordinary_memory_ring=dict(
             what="p, m, v in ordinary host memory, 6-slot pinned ring, 7 copy threads per direction",
             GBps_per_direction=round(12 * n / min(ring) / 1e9, 2),
-            frac_of_bidir_peak=round(12 * n / min(ring) / 1e9 / peaks["bidir"], 4)))
+            frac_of_bidir_peak=round(12 * n / min(ring) / 1e9 / peaks["bidir"], 4)),
+        file_tier=file_tier)
+
+
+def file_tier_figures(args, zi, eng, spec, g, lp, w, cfg):
+    """p, m, v in three files opened for direct I/O: the step's rate beside the storage's own two-way rate.
+    The disk of the box is whatever it is (not an NVMe array); the fraction is the figure.  Any I/O
+    problem (no space, no direct I/O on the file system) is reported, not fatal."""
+    import tempfile
+    import numpy as np
+    n = min(args.file_numel, g.numel())
+    if n <= 0:
+        return None
+    n -= n % 1024                                   # 4096-byte multiple per array for the probe
+    log(f"streamed: file tier, 3 x {4 * n / 2**30:.1f} GiB in {tempfile.gettempdir()}")
+    fds = []
+    try:
+        with tempfile.TemporaryDirectory() as tmp:
+            try:
+                buf = np.empty(min(n, 1 << 26), np.float32)
+                paths = [os.path.join(tmp, k + ".bin") for k in "pmv"]
+                for path, fill in zip(paths, (spec.fill_p, spec.fill_m, spec.fill_v)):
+                    with open(path, "wb") as f:
+                        for lo in range(0, n, buf.size):
+                            c = min(buf.size, n - lo)
+                            fill(buf, c, 0, lo)
+                            f.write(buf[:c].tobytes())
+                os.sync()
+                fds = [os.open(p, os.O_RDWR | os.O_DIRECT) for p in paths]
+                fds.append(os.open(os.path.join(tmp, "scratch.bin"), os.O_RDWR | os.O_CREAT | os.O_DIRECT, 0o600))
+                zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 8)
+                zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 6)
+                nbytes = 4 * n
+                zi.zi_engine_file_probe(eng, -1, fds[3], nbytes)           # allocate the scratch file's blocks
+                rd = nbytes / zi.zi_engine_file_probe(eng, fds[0], -1, nbytes) / 1e9
+                wr = nbytes / zi.zi_engine_file_probe(eng, -1, fds[3], nbytes) / 1e9
+                both = nbytes / zi.zi_engine_file_probe(eng, fds[1], fds[3], nbytes) / 1e9
+                secs = []
+                for _ in range(2):
+                    zi.zi_adamw_step_files(eng, [(fds[0], fds[1], fds[2], 0, 0, 0, g, lp, n)], w["lp_dtype"], cfg)
+                    secs.append(zi.zi_engine_last_stats(eng).seconds)
+                rate = 12 * n / min(secs) / 1e9
+                return dict(what=f"p, m, v of {n} elements in files (O_DIRECT), 6-slot pinned ring, 8 I/O threads per "
+                                 "direction; storage rates from the engine's own probe on the same files",
+                            storage_GBps=dict(read=round(rd, 2), write=round(wr, 2), both_each=round(both, 2)),
+                            step_GBps_per_direction=round(rate, 2), frac_of_two_way_storage_rate=round(rate / both, 4),
+                            params_per_s=n / min(secs))
+            finally:
+                for fd in fds:
+                    os.close(fd)
+    except (OSError, zi.ZiError) as e:
+        return dict(error=f"{type(e).__name__}: {e}")
 
 
 def cpu_baseline(args, zs):
