@@ -113,8 +113,8 @@ typedef struct {
     void* p;               /* fp32 master parameters, updated in place */
     void* m;               /* fp32 momentum, updated in place */
     void* v;               /* fp32 variance, updated in place */
-    const void* g;         /* low-precision gradients (device), read only */
-    void* p_lp;            /* low-precision parameter copy (device), written; may be NULL */
+    const void* g;         /* low-precision gradients, read only (device; the streamed calls also take host) */
+    void* p_lp;            /* low-precision parameter copy, written; may be NULL (device; streamed: or host) */
     int64_t numel;
 } zi_tensor;
 
@@ -281,7 +281,7 @@ zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
  * to finish.  The default 2 keeps copy-in and copy-out in lockstep, which measured fastest and
  * steadiest; with n_slots = 3 the third slot then only decouples the host's issue from completion.
  * ZI_OPT_HOST_RING_SLOTS = n gives the engine a ring of n pinned host slots
- * (each 3 arrays of the chunk size) and two small CPU thread pools.  With it,
+ * (each shaped like an HBM slot: 4 arrays of the chunk size) and two small CPU thread pools.  With it,
  * zi_adamw_step_streamed also accepts p, m, v in ORDINARY (pageable) host
  * memory: each chunk is copied into a ring slot by CPU threads, moved to HBM
  * and back by the copy engines, and copied out again, all stages overlapped
