@@ -56,11 +56,13 @@
  *     buffer untouched unless stated otherwise.  Nothing throws or aborts.
  *     zi_last_error() gives the text of the calling thread's last error.
  *   - Pointers must be aligned to their element size (4 bytes for p/m/v, 2
- *     bytes for g and p_lp).  The wide path needs an element index at which
- *     the fp32 arrays are 16-byte aligned and the 2-byte arrays 8-byte aligned:
- *     true for aligned arrays and for any common misalignment (all arrays
- *     offset by the same number of elements, modulo 4).  Any other placement
- *     takes a slower element-wise path with identical results.
+ *     bytes for g and p_lp); nothing more is required.  The step is fastest
+ *     when all arrays of a tensor sit at the same offset from a 128-byte
+ *     boundary, counted in elements (true for separately allocated arrays and
+ *     for views that start at the same element of aligned buffers): then all
+ *     of its traffic runs in whole 128-byte lines.  Other placements use the
+ *     same kernel and give identical results, within a few percent of that
+ *     speed.
  *   - numel == 0 and n_tensors == 0 are valid and do nothing.
  *   - Threads: calls that do not share buffers or an engine may run concurrently from different
  *     threads.  An engine serves one call at a time.  zi_last_error() is per thread.

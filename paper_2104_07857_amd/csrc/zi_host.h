@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <initializer_list>
 #include <cstdint>
 #include <vector>
 
@@ -93,17 +94,28 @@ inline zi::StepConsts make_consts(const zi_adamw_config& c)
     return k;
 }
 
-// Number of leading elements (0..3) before the index at which the fp32 arrays are 16-byte aligned
-// and the 2-byte arrays 8-byte aligned, or -1 if the arrays have no common such index (then only
-// the element-wise kernel applies).
-inline int common_head(const void* p, const void* m, const void* v, const void* g, const void* p_lp)
+// Number of leading elements (0..63) the step handles one by one before its vector body.  Any value
+// is legal: the body's vector accesses need only element alignment.  The choice decides how much of
+// the body's traffic starts on a 128-byte line (a wavefront's run then covers whole lines) and,
+// failing that, on a lane-vector boundary (16 bytes for fp32, 8 for the 2-byte arrays); arrays are
+// weighted by the bytes they move per element (p, m, v: 8; g, p_lp: 2).
+inline int choose_head(const void* p, const void* m, const void* v, const void* g, const void* p_lp)
 {
-    const int h = (int)((4 - (reinterpret_cast<uintptr_t>(g) / 2) % 4) % 4);
-    if (p_lp && (int)((4 - (reinterpret_cast<uintptr_t>(p_lp) / 2) % 4) % 4) != h) return -1;
-    const void* f[3] = {p, m, v};
-    for (const void* x : f)
-        if ((int)((4 - (reinterpret_cast<uintptr_t>(x) / 4) % 4) % 4) != h) return -1;
-    return h;
+    int best_h = 0, best = -1;
+    for (int h = 0; h < 64; ++h) {
+        int score = 0;
+        for (const void* x : {p, m, v}) {
+            const uintptr_t i = reinterpret_cast<uintptr_t>(x) / 4 + (uintptr_t)h;
+            score += 8 * (i % 32 == 0 ? 4 : i % 4 == 0 ? 1 : 0);
+        }
+        for (const void* x : {g, (const void*)p_lp}) {
+            if (!x) continue;
+            const uintptr_t i = reinterpret_cast<uintptr_t>(x) / 2 + (uintptr_t)h;
+            score += 2 * (i % 64 == 0 ? 4 : i % 4 == 0 ? 1 : 0);
+        }
+        if (score > best) { best = score; best_h = h; }
+    }
+    return best_h;
 }
 
 // Issues the fused step over a list of device-resident segments.
@@ -140,13 +152,7 @@ struct StepIssuer {
         if (numel <= 0) return hipSuccess;
         zi::StepDesc d{};
         d.p = p; d.m = m; d.v = v; d.g = g; d.p_lp = p_lp; d.numel = numel;
-        const int h = common_head(p, m, v, g, p_lp);
-        if (h < 0) {
-            d.head = 0;
-            d.first_tile = 0;
-            ++launches;
-            return zi::launch_step_elementwise(d, args.c, args.d_norm, dt, l2, stream);
-        }
+        const int h = choose_head(p, m, v, g, p_lp);
         d.head = (int32_t)(h < numel ? h : numel);
         const int64_t nquad = (numel - d.head) / zi::kQuad;
         int64_t nt = (nquad + zi::kStepTileQuads - 1) / zi::kStepTileQuads;

@@ -56,8 +56,8 @@ struct StepConsts {
 };
 
 // One tensor (or one segment of one) as the fused step sees it.  All pointers are device memory.
-// `head` elements come before the first index at which the fp32 arrays are 16-byte aligned and the
-// 2-byte arrays 8-byte aligned.
+// The first `head` elements are handled one by one; the 4-element lane vectors start after them
+// (the host picks `head` so that as much of the traffic as possible starts on a 128-byte line).
 struct StepDesc {
     float* p;
     float* m;
@@ -65,7 +65,7 @@ struct StepDesc {
     const uint16_t* g;
     uint16_t* p_lp;        // may be null
     int64_t numel;
-    int32_t head;          // 0..3
+    int32_t head;          // 0..63
     uint32_t first_tile;   // index of this tensor's first tile within the launch
 };
 
@@ -94,8 +94,6 @@ struct NormArgs {
 
 // Launchers (zi_kernels.hip).  Each returns the hipError_t of the launch.
 hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2, hipStream_t s);
-hipError_t launch_step_elementwise(const StepDesc& d, const StepConsts& c, const zi_norm_result* d_norm, int dt,
-                                   bool l2, hipStream_t s);
 hipError_t launch_norm_partials(const NormArgs& a, uint32_t n_blocks, int dt, hipStream_t s);
 hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, float loss_scale, int accumulate,
                                 zi_norm_result* d_out, hipStream_t s);

@@ -113,6 +113,11 @@ __device__ __forceinline__ void step_scalar_at(const StepDesc& T, int64_t i, flo
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// The fused step's lane vectors as they sit in memory: only element alignment is promised (gfx950
+// runs global loads and stores of any alignment as one instruction; the host picks the body's
+// start so that as many arrays as possible are line-aligned anyway).
+typedef f32x4 f32x4_mem __attribute__((aligned(4)));
+typedef u32x2 u32x2_mem __attribute__((aligned(2)));
 
 // Streaming accesses: the data is touched once, so it should not displace anything in the caches.
 // (The two switches exist for tuning builds; the defaults are the measured best.)
@@ -133,6 +138,40 @@ __device__ __forceinline__ V load_stream(const V* a)
 }
 template <typename V>
 __device__ __forceinline__ void store_stream(V* a, V x)
+{
+#if ZI_NT_STORE
+    __builtin_nontemporal_store(x, a);
+#else
+    *a = x;
+#endif
+}
+// The same for the element-aligned lane vectors (written out: an alignment attribute on a typedef
+// does not survive template argument deduction).
+__device__ __forceinline__ f32x4 load_stream_any(const f32x4_mem* a)
+{
+#if ZI_NT_LOAD
+    return __builtin_nontemporal_load(a);
+#else
+    return *a;
+#endif
+}
+__device__ __forceinline__ u32x2 load_stream_any(const u32x2_mem* a)
+{
+#if ZI_NT_LOAD
+    return __builtin_nontemporal_load(a);
+#else
+    return *a;
+#endif
+}
+__device__ __forceinline__ void store_stream_any(f32x4_mem* a, f32x4 x)
+{
+#if ZI_NT_STORE
+    __builtin_nontemporal_store(x, a);
+#else
+    *a = x;
+#endif
+}
+__device__ __forceinline__ void store_stream_any(u32x2_mem* a, u32x2 x)
 {
 #if ZI_NT_STORE
     __builtin_nontemporal_store(x, a);
@@ -183,7 +222,7 @@ __global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs
     const int64_t nquad = (T.numel - head) / kQuad;        // whole quads of the aligned body
     const int64_t body_end = head + nquad * kQuad;
 
-    // Elements before and after the aligned body (at most 3 each), by the tensor's first tile.
+    // Elements before the vector body (at most 63) and after it (at most 3), by the tensor's first tile.
     if (tile == 0) {
         const int64_t t = threadIdx.x;
         if (t < head) step_scalar_at<DT, L2>(T, t, gscale, a.c);
@@ -191,11 +230,11 @@ __global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs
         if (t >= 4 && t - 4 < tail) step_scalar_at<DT, L2>(T, body_end + (t - 4), gscale, a.c);
     }
 
-    f32x4* __restrict__ p4 = reinterpret_cast<f32x4*>(T.p + head);
-    f32x4* __restrict__ m4 = reinterpret_cast<f32x4*>(T.m + head);
-    f32x4* __restrict__ v4 = reinterpret_cast<f32x4*>(T.v + head);
-    const u32x2* __restrict__ g2 = reinterpret_cast<const u32x2*>(T.g + head);
-    u32x2* __restrict__ lp2 = T.p_lp ? reinterpret_cast<u32x2*>(T.p_lp + head) : nullptr;
+    f32x4_mem* __restrict__ p4 = reinterpret_cast<f32x4_mem*>(T.p + head);
+    f32x4_mem* __restrict__ m4 = reinterpret_cast<f32x4_mem*>(T.m + head);
+    f32x4_mem* __restrict__ v4 = reinterpret_cast<f32x4_mem*>(T.v + head);
+    const u32x2_mem* __restrict__ g2 = reinterpret_cast<const u32x2_mem*>(T.g + head);
+    u32x2_mem* __restrict__ lp2 = T.p_lp ? reinterpret_cast<u32x2_mem*>(T.p_lp + head) : nullptr;
 
     // XCD-aware renumbering (a bijection on the complete runs of 8 * kStepXcdRun tiles; the few
     // tiles after the last complete run keep their numbers).
@@ -217,46 +256,34 @@ __global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
             const int64_t i = q0 + (int64_t)u * kStepThreads;
-            g[u] = load_stream(g2 + i);
-            p[u] = load_stream(p4 + i);
-            m[u] = load_stream(m4 + i);
-            v[u] = load_stream(v4 + i);
+            g[u] = load_stream_any(g2 + i);
+            p[u] = load_stream_any(p4 + i);
+            m[u] = load_stream_any(m4 + i);
+            v[u] = load_stream_any(v4 + i);
         }
 #pragma unroll
         for (int u = 0; u < kStepUnroll; ++u) {
             const int64_t i = q0 + (int64_t)u * kStepThreads;
             const u32x2 lp = step_quad<DT, L2>(p[u], m[u], v[u], g[u], gscale, a.c);
-            store_stream(p4 + i, p[u]);
-            store_stream(m4 + i, m[u]);
-            store_stream(v4 + i, v[u]);
-            if (lp2) store_stream(lp2 + i, lp);
+            store_stream_any(p4 + i, p[u]);
+            store_stream_any(m4 + i, m[u]);
+            store_stream_any(v4 + i, v[u]);
+            if (lp2) store_stream_any(lp2 + i, lp);
         }
     } else {
         for (int u = 0; u < kStepUnroll; ++u) {
             const int64_t i = q0 + (int64_t)u * kStepThreads;
             if (i < nquad) {
-                const u32x2 g = load_stream(g2 + i);
-                f32x4 p = load_stream(p4 + i), m = load_stream(m4 + i), v = load_stream(v4 + i);
+                const u32x2 g = load_stream_any(g2 + i);
+                f32x4 p = load_stream_any(p4 + i), m = load_stream_any(m4 + i), v = load_stream_any(v4 + i);
                 const u32x2 lp = step_quad<DT, L2>(p, m, v, g, gscale, a.c);
-                store_stream(p4 + i, p);
-                store_stream(m4 + i, m);
-                store_stream(v4 + i, v);
-                if (lp2) store_stream(lp2 + i, lp);
+                store_stream_any(p4 + i, p);
+                store_stream_any(m4 + i, m);
+                store_stream_any(v4 + i, v);
+                if (lp2) store_stream_any(lp2 + i, lp);
             }
         }
     }
-}
-
-// Any placement of the arrays: one element per thread per iteration, grid-stride.
-template <int DT, bool L2>
-__global__ __launch_bounds__(kThreads) void adamw_elementwise_kernel(const StepDesc T, const StepConsts c,
-                                                                     const zi_norm_result* d_norm)
-{
-    float gscale;
-    if (!step_prologue(d_norm, c, gscale)) return;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < T.numel; i += stride)
-        step_scalar_at<DT, L2>(T, i, gscale, c);
 }
 
 hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2, hipStream_t s)
@@ -269,23 +296,6 @@ hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2
     } else {
         if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, true>), grid, block, kStepOccupancyLds, s, a);
         else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, false>), grid, block, kStepOccupancyLds, s, a);
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_step_elementwise(const StepDesc& d, const StepConsts& c, const zi_norm_result* d_norm, int dt,
-                                   bool l2, hipStream_t s)
-{
-    if (d.numel <= 0) return hipSuccess;
-    int64_t blocks = (d.numel + kThreads - 1) / kThreads;
-    if (blocks > 65536) blocks = 65536;
-    const dim3 grid((uint32_t)blocks), block(kThreads);
-    if (dt == ZI_BF16) {
-        if (l2) hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_BF16, true>), grid, block, 0, s, d, c, d_norm);
-        else    hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_BF16, false>), grid, block, 0, s, d, c, d_norm);
-    } else {
-        if (l2) hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_FP16, true>), grid, block, 0, s, d, c, d_norm);
-        else    hipLaunchKernelGGL((adamw_elementwise_kernel<ZI_FP16, false>), grid, block, 0, s, d, c, d_norm);
     }
     return hipGetLastError();
 }

@@ -33,12 +33,12 @@ def _draw_case(rng):
     n_tensors = int(rng.integers(1, 6))
     sizes = [int(rng.choice([0, 1, int(rng.integers(2, 600)), int(rng.integers(600, 70_000))]))
              for _ in range(n_tensors)]
-    # alignment: one common offset (wide kernel with scalar ends) or unrelated ones (element-wise kernel)
+    # alignment: one common offset (every array line-aligned after the leading elements) or unrelated ones
     if rng.random() < 0.6:
-        k = int(rng.integers(0, 8))
+        k = int(rng.integers(0, 70))
         offsets = [(k,) * 5 for _ in sizes]
     else:
-        offsets = [tuple(int(x) for x in rng.integers(0, 8, 5)) for _ in sizes]
+        offsets = [tuple(int(x) for x in rng.integers(0, 70, 5)) for _ in sizes]
     g_std = 1e-3 * loss_scale * float(rng.choice([0.1, 1.0, 10.0]))
     if dt == zi.ZI_FP16:
         g_std = min(g_std, 2000.0)         # keep 6 sigma below the largest fp16 value
@@ -47,7 +47,7 @@ def _draw_case(rng):
     return dt, hp, sizes, offsets, g_std, with_lp, use_norm
 
 
-def _place(a, off, pad=16):
+def _place(a, off, pad=80):
     t = torch.zeros(a.size + pad, dtype=torch.float32 if a.dtype == np.float32 else torch.int16, device="cuda:0")
     t[off:off + a.size].copy_(to_dev(a))
     return t, t[off:off + a.size]

@@ -24,7 +24,7 @@ def _run_both(p, m, v, g, dt, ocfg, zcfg, with_lp=True, use_norm=False, offsets=
         sumsq, flag = oracle.grad_sumsq([g], dt)
     rc = oracle.adamw(pe, me, ve, g, lpe, dt, ocfg, sumsq, flag)
 
-    pad = 16
+    pad = 80
     off = offsets or (0, 0, 0, 0, 0)
     bufs = []
     for a, o in zip((p, m, v, g, np.zeros(n, np.uint16)), off):
@@ -92,8 +92,9 @@ def test_without_low_precision_copy():
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6, 7])
-def test_common_misalignment_takes_the_wide_path_with_scalar_ends(k):
-    """All five arrays start k elements past a 16-byte boundary (a slice of a flat partition)."""
+def test_common_misalignment(k):
+    """All five arrays start k elements past an aligned address (a slice of a flat partition): the
+    vector body then starts 64 - k elements in, on a 128-byte line of every array."""
     n = 3 * TILE + 11
     w = zi_synth.workload("c1")
     p, m, v, g = gen_numpy(zi_synth.StateSpec(500 + k, zi.ZI_BF16), n)
@@ -102,8 +103,10 @@ def test_common_misalignment_takes_the_wide_path_with_scalar_ends(k):
 
 
 @pytest.mark.parametrize("offsets", [(1, 0, 0, 0, 0), (0, 0, 0, 1, 0), (0, 0, 0, 0, 3), (1, 2, 3, 5, 7),
-                                     (4, 4, 4, 0, 0), (0, 0, 0, 4, 4)])
-def test_unrelated_misalignments_take_the_elementwise_path(offsets):
+                                     (4, 4, 4, 0, 0), (0, 0, 0, 4, 4), (0, 0, 0, 32, 32), (3, 3, 3, 35, 35),
+                                     (31, 30, 29, 63, 1)])
+def test_unrelated_misalignments(offsets):
+    """Arrays with no common alignment: the lane vectors of some arrays are then only element-aligned."""
     n = 2 * TILE + 77
     w = zi_synth.workload("c1")
     p, m, v, g = gen_numpy(zi_synth.StateSpec(900 + sum(offsets), zi.ZI_BF16), n)
