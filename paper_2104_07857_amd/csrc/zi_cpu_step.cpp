@@ -10,10 +10,12 @@
 // the default MXCSR keeps denormals.  Compiled by the host compiler with -ffp-contract=off.
 #include <immintrin.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <exception>
 #include <thread>
 #include <vector>
 
@@ -139,7 +141,13 @@ void parallel_blocks(int64_t n_blocks, int n_threads, F fn)
     };
     std::vector<std::thread> th;
     const int extra = (int)std::min<int64_t>(n_threads - 1, n_blocks - 1);
-    for (int i = 0; i < extra; ++i) th.emplace_back(work);
+    for (int i = 0; i < extra; ++i) {
+        try {
+            th.emplace_back(work);
+        } catch (const std::exception&) {
+            break;          // fewer threads than asked for; the result does not depend on the count
+        }
+    }
     work();
     for (auto& t : th) t.join();
 }
@@ -166,135 +174,143 @@ zi_status check_common(const zi_tensor* t, int32_t n_tensors, int dt, int32_t n_
 extern "C" zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
                                        zi_norm_result* h_out, int32_t n_threads)
 {
-    if (zi_status st = check_common(t, n_tensors, (int)dt, n_threads)) return st;
-    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
-        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
-    if (!h_out) return fail(ZI_ERR_INVALID_ARG, "h_out is NULL");
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-        if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
-        if (reinterpret_cast<uintptr_t>(t[i].g) % 2) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
-    }
-    // One partial per block, summed in block order afterwards: the result does not depend on the
-    // number of threads.
-    struct Block { int32_t tensor; int64_t lo, hi; };
-    std::vector<Block> blocks;
-    for (int32_t i = 0; i < n_tensors; ++i)
-        for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
-            blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
-    std::vector<double> part(blocks.size(), 0.0);
-    std::vector<uint8_t> flag(blocks.size(), 0);
-    const uint16_t expmask = dt == ZI_BF16 ? 0x7F80u : 0x7C00u;
-    parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
-        const Block& B = blocks[(size_t)b];
-        const uint16_t* g = (const uint16_t*)t[B.tensor].g;
-        __m256d acc0 = _mm256_setzero_pd(), acc1 = _mm256_setzero_pd();
-        __m128i bad = _mm_setzero_si128();
-        const __m128i em = _mm_set1_epi16((short)expmask);
-        int64_t i = B.lo;
-        for (; i + 8 <= B.hi; i += 8) {
-            const __m128i h = _mm_loadu_si128((const __m128i*)(g + i));
-            bad = _mm_or_si128(bad, _mm_cmpeq_epi16(_mm_and_si128(h, em), em));
-            const __m256 f = dt == ZI_BF16 ? widen8<ZI_BF16>(g + i) : widen8<ZI_FP16>(g + i);
-            const __m256d lo = _mm256_cvtps_pd(_mm256_castps256_ps128(f));
-            const __m256d hi = _mm256_cvtps_pd(_mm256_extractf128_ps(f, 1));
-            acc0 = _mm256_fmadd_pd(lo, lo, acc0);
-            acc1 = _mm256_fmadd_pd(hi, hi, acc1);
+    try {
+        if (zi_status st = check_common(t, n_tensors, (int)dt, n_threads)) return st;
+        if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
+            return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+        if (!h_out) return fail(ZI_ERR_INVALID_ARG, "h_out is NULL");
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+            if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
+            if (reinterpret_cast<uintptr_t>(t[i].g) % 2) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
         }
-        double lanes[4];
-        _mm256_storeu_pd(lanes, _mm256_add_pd(acc0, acc1));
-        double s = (lanes[0] + lanes[1]) + (lanes[2] + lanes[3]);
-        bool f = !_mm_testz_si128(bad, bad);
-        for (; i < B.hi; ++i) {
-            if ((g[i] & expmask) == expmask) f = true;
-            const double x = (double)widen_scalar(g[i], (int)dt);
-            s = std::fma(x, x, s);
+        // One partial per block, summed in block order afterwards: the result does not depend on the
+        // number of threads.
+        struct Block { int32_t tensor; int64_t lo, hi; };
+        std::vector<Block> blocks;
+        for (int32_t i = 0; i < n_tensors; ++i)
+            for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
+                blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
+        std::vector<double> part(blocks.size(), 0.0);
+        std::vector<uint8_t> flag(blocks.size(), 0);
+        const uint16_t expmask = dt == ZI_BF16 ? 0x7F80u : 0x7C00u;
+        parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
+            const Block& B = blocks[(size_t)b];
+            const uint16_t* g = (const uint16_t*)t[B.tensor].g;
+            __m256d acc0 = _mm256_setzero_pd(), acc1 = _mm256_setzero_pd();
+            __m128i bad = _mm_setzero_si128();
+            const __m128i em = _mm_set1_epi16((short)expmask);
+            int64_t i = B.lo;
+            for (; i + 8 <= B.hi; i += 8) {
+                const __m128i h = _mm_loadu_si128((const __m128i*)(g + i));
+                bad = _mm_or_si128(bad, _mm_cmpeq_epi16(_mm_and_si128(h, em), em));
+                const __m256 f = dt == ZI_BF16 ? widen8<ZI_BF16>(g + i) : widen8<ZI_FP16>(g + i);
+                const __m256d lo = _mm256_cvtps_pd(_mm256_castps256_ps128(f));
+                const __m256d hi = _mm256_cvtps_pd(_mm256_extractf128_ps(f, 1));
+                acc0 = _mm256_fmadd_pd(lo, lo, acc0);
+                acc1 = _mm256_fmadd_pd(hi, hi, acc1);
+            }
+            double lanes[4];
+            _mm256_storeu_pd(lanes, _mm256_add_pd(acc0, acc1));
+            double s = (lanes[0] + lanes[1]) + (lanes[2] + lanes[3]);
+            bool f = !_mm_testz_si128(bad, bad);
+            for (; i < B.hi; ++i) {
+                if ((g[i] & expmask) == expmask) f = true;
+                const double x = (double)widen_scalar(g[i], (int)dt);
+                s = std::fma(x, x, s);
+            }
+            part[(size_t)b] = s;
+            flag[(size_t)b] = f;
+        });
+        double sum = 0.0;
+        uint32_t found = 0;
+        for (size_t b = 0; b < blocks.size(); ++b) {
+            sum += part[b];
+            found |= flag[b];
         }
-        part[(size_t)b] = s;
-        flag[(size_t)b] = f;
-    });
-    double sum = 0.0;
-    uint32_t found = 0;
-    for (size_t b = 0; b < blocks.size(); ++b) {
-        sum += part[b];
-        found |= flag[b];
+        h_out->sumsq = sum;
+        h_out->norm = std::sqrt(sum) / (double)loss_scale;
+        h_out->found_inf = found ? 1u : 0u;
+        h_out->reserved = 0;
+        return ZI_OK;
+    } catch (const std::exception& ex) {
+        return fail(ZI_ERR_NOMEM, "host step: %s", ex.what());
     }
-    h_out->sumsq = sum;
-    h_out->norm = std::sqrt(sum) / (double)loss_scale;
-    h_out->found_inf = found ? 1u : 0u;
-    h_out->reserved = 0;
-    return ZI_OK;
 }
 
 extern "C" zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                                         const zi_adamw_config* cfg, const zi_norm_result* h_norm,
                                         int32_t n_threads)
 {
-    if (zi_status st = check_common(t, n_tensors, (int)dt, n_threads)) return st;
-    if (!cfg) return fail(ZI_ERR_INVALID_ARG, "cfg is NULL");
-    if (cfg->step < 1) return fail(ZI_ERR_INVALID_ARG, "step must be >= 1");
-    if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f) || !(cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f))
-        return fail(ZI_ERR_INVALID_ARG, "betas must be in [0,1)");
-    if (!(cfg->eps >= 0.0f) || std::isinf(cfg->eps)) return fail(ZI_ERR_INVALID_ARG, "eps must be finite and >= 0");
-    if (!std::isfinite(cfg->lr) || !std::isfinite(cfg->weight_decay))
-        return fail(ZI_ERR_INVALID_ARG, "lr and weight_decay must be finite");
-    if (!(cfg->loss_scale > 0.0f) || std::isinf(cfg->loss_scale))
-        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
-    if (std::isnan(cfg->max_grad_norm)) return fail(ZI_ERR_INVALID_ARG, "max_grad_norm is NaN");
-    if (cfg->mode != ZI_MODE_ADAMW && cfg->mode != ZI_MODE_ADAM_L2) return fail(ZI_ERR_INVALID_ARG, "unknown mode");
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-        if (t[i].numel == 0) continue;
-        if (!t[i].p || !t[i].m || !t[i].v || !t[i].g)
-            return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v and g must not be NULL", i);
-        if (reinterpret_cast<uintptr_t>(t[i].p) % 4 || reinterpret_cast<uintptr_t>(t[i].m) % 4 ||
-            reinterpret_cast<uintptr_t>(t[i].v) % 4)
-            return fail(ZI_ERR_ALIGNMENT, "tensor %d: p, m, v must be 4-byte aligned", i);
-        if (reinterpret_cast<uintptr_t>(t[i].g) % 2 || reinterpret_cast<uintptr_t>(t[i].p_lp) % 2)
-            return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
-    }
-    if (h_norm && h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
-
-    // per-step scalars: double, each rounded once to fp32 (same expressions as the GPU path's host side)
-    Consts c{};
-    const double b1 = (double)cfg->beta1, b2 = (double)cfg->beta2;
-    const double bc1 = 1.0 - std::pow(b1, (double)cfg->step);
-    const double bc2 = 1.0 - std::pow(b2, (double)cfg->step);
-    c.beta1 = cfg->beta1;
-    c.beta2 = cfg->beta2;
-    c.omb1 = (float)(1.0 - b1);
-    c.omb2 = (float)(1.0 - b2);
-    c.eps = cfg->eps;
-    c.step_size = (float)((double)cfg->lr / bc1);
-    c.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
-    c.l2 = cfg->mode == ZI_MODE_ADAM_L2;
-    c.decay = c.l2 ? 0.0f : (float)((double)cfg->lr * (double)cfg->weight_decay);
-    c.weight_decay = cfg->weight_decay;
-    double clip = 1.0;
-    if (h_norm) {
-        const double mx = (double)cfg->max_grad_norm;
-        if (cfg->max_grad_norm > 0.0f && h_norm->norm + 1e-6 > mx) clip = mx / (h_norm->norm + 1e-6);
-    }
-    c.gscale = (float)(clip / (double)cfg->loss_scale);
-
-    struct Block { int32_t tensor; int64_t lo, hi; };
-    std::vector<Block> blocks;
-    for (int32_t i = 0; i < n_tensors; ++i)
-        for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
-            blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
-    parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
-        const Block& B = blocks[(size_t)b];
-        const zi_tensor& T = t[B.tensor];
-        float *p = (float*)T.p, *m = (float*)T.m, *v = (float*)T.v;
-        const uint16_t* g = (const uint16_t*)T.g;
-        uint16_t* lp = (uint16_t*)T.p_lp;
-        if (dt == ZI_BF16) {
-            if (c.l2) step_range<ZI_BF16, true>(p, m, v, g, lp, B.lo, B.hi, c);
-            else      step_range<ZI_BF16, false>(p, m, v, g, lp, B.lo, B.hi, c);
-        } else {
-            if (c.l2) step_range<ZI_FP16, true>(p, m, v, g, lp, B.lo, B.hi, c);
-            else      step_range<ZI_FP16, false>(p, m, v, g, lp, B.lo, B.hi, c);
+    try {
+        if (zi_status st = check_common(t, n_tensors, (int)dt, n_threads)) return st;
+        if (!cfg) return fail(ZI_ERR_INVALID_ARG, "cfg is NULL");
+        if (cfg->step < 1) return fail(ZI_ERR_INVALID_ARG, "step must be >= 1");
+        if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f) || !(cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f))
+            return fail(ZI_ERR_INVALID_ARG, "betas must be in [0,1)");
+        if (!(cfg->eps >= 0.0f) || std::isinf(cfg->eps)) return fail(ZI_ERR_INVALID_ARG, "eps must be finite and >= 0");
+        if (!std::isfinite(cfg->lr) || !std::isfinite(cfg->weight_decay))
+            return fail(ZI_ERR_INVALID_ARG, "lr and weight_decay must be finite");
+        if (!(cfg->loss_scale > 0.0f) || std::isinf(cfg->loss_scale))
+            return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+        if (std::isnan(cfg->max_grad_norm)) return fail(ZI_ERR_INVALID_ARG, "max_grad_norm is NaN");
+        if (cfg->mode != ZI_MODE_ADAMW && cfg->mode != ZI_MODE_ADAM_L2) return fail(ZI_ERR_INVALID_ARG, "unknown mode");
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
+            if (t[i].numel == 0) continue;
+            if (!t[i].p || !t[i].m || !t[i].v || !t[i].g)
+                return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v and g must not be NULL", i);
+            if (reinterpret_cast<uintptr_t>(t[i].p) % 4 || reinterpret_cast<uintptr_t>(t[i].m) % 4 ||
+                reinterpret_cast<uintptr_t>(t[i].v) % 4)
+                return fail(ZI_ERR_ALIGNMENT, "tensor %d: p, m, v must be 4-byte aligned", i);
+            if (reinterpret_cast<uintptr_t>(t[i].g) % 2 || reinterpret_cast<uintptr_t>(t[i].p_lp) % 2)
+                return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
         }
-    });
-    return ZI_OK;
+        if (h_norm && h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
+
+        // per-step scalars: double, each rounded once to fp32 (same expressions as the GPU path's host side)
+        Consts c{};
+        const double b1 = (double)cfg->beta1, b2 = (double)cfg->beta2;
+        const double bc1 = 1.0 - std::pow(b1, (double)cfg->step);
+        const double bc2 = 1.0 - std::pow(b2, (double)cfg->step);
+        c.beta1 = cfg->beta1;
+        c.beta2 = cfg->beta2;
+        c.omb1 = (float)(1.0 - b1);
+        c.omb2 = (float)(1.0 - b2);
+        c.eps = cfg->eps;
+        c.step_size = (float)((double)cfg->lr / bc1);
+        c.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
+        c.l2 = cfg->mode == ZI_MODE_ADAM_L2;
+        c.decay = c.l2 ? 0.0f : (float)((double)cfg->lr * (double)cfg->weight_decay);
+        c.weight_decay = cfg->weight_decay;
+        double clip = 1.0;
+        if (h_norm) {
+            const double mx = (double)cfg->max_grad_norm;
+            if (cfg->max_grad_norm > 0.0f && h_norm->norm + 1e-6 > mx) clip = mx / (h_norm->norm + 1e-6);
+        }
+        c.gscale = (float)(clip / (double)cfg->loss_scale);
+
+        struct Block { int32_t tensor; int64_t lo, hi; };
+        std::vector<Block> blocks;
+        for (int32_t i = 0; i < n_tensors; ++i)
+            for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
+                blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
+        parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
+            const Block& B = blocks[(size_t)b];
+            const zi_tensor& T = t[B.tensor];
+            float *p = (float*)T.p, *m = (float*)T.m, *v = (float*)T.v;
+            const uint16_t* g = (const uint16_t*)T.g;
+            uint16_t* lp = (uint16_t*)T.p_lp;
+            if (dt == ZI_BF16) {
+                if (c.l2) step_range<ZI_BF16, true>(p, m, v, g, lp, B.lo, B.hi, c);
+                else      step_range<ZI_BF16, false>(p, m, v, g, lp, B.lo, B.hi, c);
+            } else {
+                if (c.l2) step_range<ZI_FP16, true>(p, m, v, g, lp, B.lo, B.hi, c);
+                else      step_range<ZI_FP16, false>(p, m, v, g, lp, B.lo, B.hi, c);
+            }
+        });
+        return ZI_OK;
+    } catch (const std::exception& ex) {
+        return fail(ZI_ERR_NOMEM, "host step: %s", ex.what());
+    }
 }

@@ -82,6 +82,16 @@ zi_status check_engine(const zi_engine* e)
     return ZI_OK;
 }
 
+// A pool of `n` copy threads, or null if memory or threads cannot be had.
+CopyPool* make_pool(int n)
+{
+    try {
+        return new CopyPool(n);
+    } catch (const std::exception&) {
+        return nullptr;
+    }
+}
+
 void ring_release(zi_engine* e)
 {
     delete e->pool_in;
@@ -210,9 +220,12 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
         if (e->pool_in) {
             delete e->pool_in;
             delete e->pool_out;
-            e->pool_in = new (std::nothrow) CopyPool(e->copy_threads);
-            e->pool_out = new (std::nothrow) CopyPool(e->copy_threads);
-            if (!e->pool_in || !e->pool_out) return fail(ZI_ERR_NOMEM, "out of host memory");
+            e->pool_in = make_pool(e->copy_threads);
+            e->pool_out = make_pool(e->copy_threads);
+            if (!e->pool_in || !e->pool_out) {
+                ring_release(e);          // the engine is left without a ring rather than with half of one
+                return fail(ZI_ERR_NOMEM, "could not start the copy threads; the pinned ring was released");
+            }
         }
         return ZI_OK;
     }
@@ -237,11 +250,11 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
                 return fail(ZI_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(he));
             }
         }
-        e->pool_in = new (std::nothrow) CopyPool(e->copy_threads);
-        e->pool_out = new (std::nothrow) CopyPool(e->copy_threads);
+        e->pool_in = make_pool(e->copy_threads);
+        e->pool_out = make_pool(e->copy_threads);
         if (!e->pool_in || !e->pool_out) {
             ring_release(e);
-            return fail(ZI_ERR_NOMEM, "out of host memory");
+            return fail(ZI_ERR_NOMEM, "could not start the copy threads");
         }
         e->n_hslots = (int)value;
         return ZI_OK;

@@ -39,9 +39,9 @@ public:
         bool bounce;
     };
 
-    explicit CopyPool(int n_threads)
+    explicit CopyPool(int n_threads) : bounce_((size_t)(n_threads < 1 ? 1 : n_threads), nullptr)
     {
-        for (int i = 1; i < n_threads; ++i) workers_.emplace_back([this] { loop(); });
+        for (int i = 1; i < n_threads; ++i) workers_.emplace_back([this, i] { loop(i); });
     }
     ~CopyPool()
     {
@@ -51,7 +51,10 @@ public:
         }
         cv_job_.notify_all();
         for (auto& w : workers_) w.join();
+        for (char* b : bounce_) std::free(b);
     }
+    CopyPool(const CopyPool&) = delete;
+    CopyPool& operator=(const CopyPool&) = delete;
     // Returns 0, or the errno of the first failed piece (EIO for a short transfer).
     int run(const std::vector<Piece>& pieces)
     {
@@ -64,7 +67,7 @@ public:
             ++generation_;
         }
         cv_job_.notify_all();
-        drain();
+        drain(0);
         std::unique_lock<std::mutex> lk(mu_);
         cv_done_.wait(lk, [this] { return pending_ == 0; });
         pieces_ = nullptr;
@@ -72,7 +75,8 @@ public:
     }
 
 private:
-    void drain()
+    // `who`: 0 = the thread that called run(), i = worker i; selects the direct-I/O buffer.
+    void drain(int who)
     {
         const std::vector<Piece>& ps = *pieces_;
         for (size_t i = next_.fetch_add(1); i < ps.size(); i = next_.fetch_add(1)) {
@@ -83,14 +87,14 @@ private:
             }
             char* io = p.mem;
             if (p.bounce) {
-                static thread_local char* tl_bounce = nullptr;
-                if (!tl_bounce && posix_memalign((void**)&tl_bounce, 4096, kCopyPieceBytes) != 0) {
-                    tl_bounce = nullptr;
+                char*& buf = bounce_[(size_t)who];
+                if (!buf && posix_memalign((void**)&buf, 4096, kCopyPieceBytes) != 0) {
+                    buf = nullptr;
                     int expected = 0;
                     error_.compare_exchange_strong(expected, ENOMEM);
                     continue;
                 }
-                io = tl_bounce;
+                io = buf;
                 if (p.op == 2) std::memcpy(io, p.mem, p.bytes);
             }
             size_t done = 0;
@@ -114,7 +118,7 @@ private:
             }
         }
     }
-    void loop()
+    void loop(int who)
     {
         uint64_t seen = 0;
         for (;;) {
@@ -124,7 +128,7 @@ private:
                 if (stop_) return;
                 seen = generation_;
             }
-            drain();
+            drain(who);
             {
                 std::lock_guard<std::mutex> lk(mu_);
                 --pending_;
@@ -133,6 +137,7 @@ private:
         }
     }
     std::vector<std::thread> workers_;
+    std::vector<char*> bounce_;         // per thread, allocated on first direct-I/O piece
     std::mutex mu_;
     std::condition_variable cv_job_, cv_done_;
     const std::vector<Piece>* pieces_ = nullptr;
@@ -142,7 +147,6 @@ private:
     int pending_ = 0;
     bool stop_ = false;
 };
-
 
 }  // namespace host
 }  // namespace zi
