@@ -230,12 +230,13 @@ zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tens
  * fd_*: descriptors open O_RDWR; the caller keeps and closes them.  off_*: byte offset of the
  * array inside its file (multiple of 4).  Descriptors opened with O_DIRECT are supported and
  * recommended for NVMe: then every offset must be a multiple of 4096, no two arrays may share a
- * 4096-byte block of a file, g must be 8-byte aligned, and transfers are rounded up to whole
+ * 4096-byte block of a file, and transfers are rounded up to whole
  * blocks (a file whose last region is not a multiple of 4096 bytes grows to the block boundary).
  * Direct I/O passes through a small per-thread aligned buffer in ordinary memory, because memory
  * from the HIP page-locked allocator cannot itself be the target of direct I/O; buffered
  * descriptors read and write the pinned ring in place.
- * g, p_lp: device memory, as in zi_adamw_step_streamed.  Blocking; data is written with pwrite,
+ * g, p_lp: device or host memory, as in zi_adamw_step_streamed (with O_DIRECT the device-resident one
+ * of them, if any, must be 8-byte aligned).  Blocking; data is written with pwrite,
  * not synced (call fsync/fdatasync if durability is needed).  Results are bit-identical to
  * zi_adamw_step on the same values.  A bad descriptor is ZI_ERR_INVALID_ARG; a failed or short read
  * or write is ZI_ERR_IO with the errno text in zi_last_error(), and part of the state may then

@@ -855,6 +855,12 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
         if (!S.g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
         if (!aligned(S.g, 2) || !aligned(S.p_lp, 2))
             return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
+        const int gk = memory_kind(S.g), lk = S.p_lp ? memory_kind(S.p_lp) : 0;
+        if (gk < 0 || lk < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g / p_lp is neither device nor host memory", i);
+        S.g_host = gk != 0;
+        S.lp_host = S.p_lp && lk != 0;
+        // the device-resident 2-byte array that sets the alignment phase of the staged arrays, if any
+        const void* phase_ref = !S.g_host ? S.g : (S.p_lp && !S.lp_host ? S.p_lp : nullptr);
         for (int w = 0; w < 3; ++w) {
             const int fl = S.fd[w] >= 0 ? fcntl(S.fd[w], F_GETFL) : -1;
             if (fl < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: bad file descriptor", i);
@@ -865,8 +871,9 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
             if (S.direct[w]) {
                 if (S.off[w] % 4096)
                     return fail(ZI_ERR_ALIGNMENT, "tensor %d: with O_DIRECT, offsets must be multiples of 4096", i);
-                if (!aligned(S.g, 8))
-                    return fail(ZI_ERR_ALIGNMENT, "tensor %d: with O_DIRECT, g must be 8-byte aligned", i);
+                if (!aligned(phase_ref, 8))
+                    return fail(ZI_ERR_ALIGNMENT, "tensor %d: with O_DIRECT, g (p_lp if g is host memory) must be "
+                                                  "8-byte aligned", i);
             }
         }
     }

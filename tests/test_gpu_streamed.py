@@ -333,10 +333,11 @@ def _write_state_files(tmp, host, direct):
     return [os.open(p, flags) for p in paths], offs, paths
 
 
-@pytest.mark.parametrize("direct", [False, True])
-def test_state_in_files_through_the_pinned_ring(direct):
+@pytest.mark.parametrize("direct,host_g", [(False, False), (True, False), (True, True), (False, True)])
+def test_state_in_files_through_the_pinned_ring(direct, host_g):
     """fp32 state in files (buffered and O_DIRECT descriptors): parallel reads into the pinned ring, the
-    same device pipeline, parallel writes back.  Bit-identical to the resident step."""
+    same device pipeline, parallel writes back.  Bit-identical to the resident step.  With host_g the
+    gradients and the low-precision copy live in ordinary host memory and ride the ring as well."""
     w = zi_synth.workload("c4")
     eng = zi.zi_engine_create(0, 64 * 1024, 3)
     fds = []
@@ -354,11 +355,17 @@ def test_state_in_files_through_the_pinned_ring(direct):
                 dlp = [torch.zeros(t[3].size, dtype=torch.int16, device="cuda:0") for t in host]
                 nb = NormBuffers()
                 zi.zi_grad_norm([(None, None, None, g, None, g.numel()) for g in dg], zi.ZI_BF16, 1.0, nb.out, nb.ws)
-                tl = [(fds[0], fds[1], fds[2], o, o, o, g, lp, g.numel()) for o, g, lp in zip(offs, dg, dlp)]
+                hlp = [np.zeros(t[3].size, np.uint16) for t in host]
+                if host_g:
+                    tl = [(fds[0], fds[1], fds[2], o, o, o, t[3], lp, t[3].size) for o, t, lp in zip(offs, host, hlp)]
+                else:
+                    tl = [(fds[0], fds[1], fds[2], o, o, o, g, lp, g.numel()) for o, g, lp in zip(offs, dg, dlp)]
                 st = zi.zi_adamw_step_files(eng, tl, zi.ZI_BF16, zi_cfg(w), nb.out, torch.cuda.current_stream())
                 assert st == zi.ZI_OK
                 stats = zi.zi_engine_last_stats(eng)
-                assert stats.bytes_h2d == 12 * sum(numel) == stats.bytes_d2h
+                assert stats.bytes_h2d == (14 if host_g else 12) * sum(numel) == stats.bytes_d2h
+                if host_g:
+                    dlp = [to_dev(a) for a in hlp]
                 for fd in fds:
                     os.close(fd)
                 fds = []
