@@ -302,7 +302,7 @@ def file_tier_figures(args, zi, eng, spec, g, lp, w, cfg):
                 os.sync()
                 fds = [os.open(p, os.O_RDWR | os.O_DIRECT) for p in paths]
                 fds.append(os.open(os.path.join(tmp, "scratch.bin"), os.O_RDWR | os.O_CREAT | os.O_DIRECT, 0o600))
-                zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 8)
+                zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 16)
                 zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 6)
                 nbytes = 4 * n
                 zi.zi_engine_file_probe(eng, -1, fds[3], nbytes)           # allocate the scratch file's blocks
@@ -314,7 +314,7 @@ def file_tier_figures(args, zi, eng, spec, g, lp, w, cfg):
                     zi.zi_adamw_step_files(eng, [(fds[0], fds[1], fds[2], 0, 0, 0, g, lp, n)], w["lp_dtype"], cfg)
                     secs.append(zi.zi_engine_last_stats(eng).seconds)
                 rate = 12 * n / min(secs) / 1e9
-                return dict(what=f"p, m, v of {n} elements in files (O_DIRECT), 6-slot pinned ring, 8 I/O threads per "
+                return dict(what=f"p, m, v of {n} elements in files (O_DIRECT), 6-slot pinned ring, 16 I/O threads per "
                                  "direction; storage rates from the engine's own probe on the same files",
                             storage_GBps=dict(read=round(rd, 2), write=round(wr, 2), both_each=round(both, 2)),
                             step_GBps_per_direction=round(rate, 2), frac_of_two_way_storage_rate=round(rate / both, 4),

@@ -287,7 +287,7 @@ def test_file_tier_one_gibi_elements_direct_io():
             fill_device_lp(lambda b, c, f: spec.fill_g(b, c, 0, f), n, g)
             lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
             eng = zi.zi_engine_create(0, w["chunk_bytes"], w["n_slots"])
-            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 8)
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, 16)
             zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 6)
             nbytes = 4 * n
             rd = nbytes / zi.zi_engine_file_probe(eng, fds[0], -1, nbytes) / 1e9
