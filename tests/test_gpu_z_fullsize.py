@@ -9,6 +9,7 @@ every bit in place.
 import ctypes
 import math
 import os
+import shutil
 import tempfile
 
 import numpy as np
@@ -219,6 +220,10 @@ def test_c2_full_8e9_in_ordinary_host_memory_through_the_pinned_ring():
     w = zi_synth.workload("c2")
     n, dt, spec = w["numel"][0], w["lp_dtype"], w["spec"]
     chunk = w["chunk_bytes"] // 4
+    import psutil
+    avail = psutil.virtual_memory().available
+    if avail < 120 * (1 << 30):
+        pytest.skip(f"needs 96 GB of host memory for the state, {avail / 2**30:.0f} GiB available")
     progress(f"c2-ring: generating 3 x {4 * n / 1e9:.0f} GB of ordinary host memory")
     hp, hm, hv = (np.empty(n, np.float32) for _ in range(3))
     piece = 1 << 30
@@ -273,6 +278,9 @@ def test_file_tier_one_gibi_elements_direct_io():
     fds = []
     with tempfile.TemporaryDirectory(dir="/tmp") as tmp:
         try:
+            free = shutil.disk_usage(tmp).free
+            if free < 20 * (1 << 30):
+                pytest.skip(f"needs 16 GiB of disk under /tmp for the state files, {free / 2**30:.0f} GiB free")
             paths = [os.path.join(tmp, k + ".bin") for k in "pmv"]
             buf = np.empty(1 << 28, np.float32)
             for path, fill in zip(paths, (spec.fill_p, spec.fill_m, spec.fill_v)):
