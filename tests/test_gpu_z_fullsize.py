@@ -67,6 +67,56 @@ def test_c1_resident_1p3e9():
     progress(f"c1: {len(ranges)} ranges of {WIDTH} verified; last: {worst}")
 
 
+def test_resident_tensor_longer_than_2_pow_32_elements():
+    """Maximum sizes: one resident tensor of 2^32 + 2^20 + 3 elements (69 GB of arrays).  Element indices
+    pass 2^31 and 2^32 inside one launch of each kernel: an overflow planted beyond 2^32 must be seen and
+    skip the step, and the step proper must match the oracle around both boundaries and at the ragged end."""
+    w = zi_synth.workload("c1")
+    dt, spec = w["lp_dtype"], w["spec"]
+    n = (1 << 32) + (1 << 20) + 3
+    progress(f"2^32+: generating {n} elements")
+    p, m, v, g, lp = device_state(spec, n)
+    nb = NormBuffers()
+    tl = [(p, m, v, g, lp, n)]
+    cfg = zi_cfg(w, max_grad_norm=1.0)
+    ranges = sample_ranges(n, WIDTH, extra_points=(1 << 31, 1 << 32, (1 << 32) + (1 << 20)), count=6, seed=9)
+    before = [device_range(p, m, v, lp, lo, hi) for lo, hi in ranges]
+
+    j = (1 << 32) + 12345
+    keep = int(g[j])
+    g[j] = 0x7F80                                   # +inf in bf16, beyond index 2^32
+    zi.zi_grad_norm(tl, dt, w["loss_scale"], nb.out, nb.ws)
+    zi.zi_adamw_step(tl, dt, cfg, nb.out)
+    torch.cuda.synchronize()
+    assert nb.read()[2] == 1
+    for (lo, hi), b in zip(ranges, before):
+        for x, y in zip(b, device_range(p, m, v, lp, lo, hi)):
+            assert np.array_equal(x.view(np.uint8), y.view(np.uint8)), f"skipped step changed [{lo},{hi})"
+    progress("2^32+: overflow beyond 2^32 seen, nothing changed")
+
+    g[j] = keep
+    zi.zi_grad_norm(tl, dt, w["loss_scale"], nb.out, nb.ws)
+    zi.zi_adamw_step(tl, dt, cfg, nb.out)
+    torch.cuda.synchronize()
+    sumsq, norm, flag = nb.read()
+    assert flag == 0
+    progress("2^32+: stepped; oracle sum of squares over 4.3e9 regenerated gradients ...")
+    hg = np.empty(n, np.uint16)
+    for lo in range(0, n, 1 << 30):
+        spec.fill_g(hg[lo:], min(1 << 30, n - lo), 0, lo)
+    osumsq, oflag = oracle.grad_sumsq([hg], dt)
+    del hg
+    onorm = math.sqrt(osumsq)
+    assert oflag == 0 and abs(norm - onorm) <= TOL_NORM_REL * onorm          # every element was counted
+    assert abs(onorm - 1e-3 * math.sqrt(n)) < 1e-2 * 1e-3 * math.sqrt(n)
+    worst = ""
+    for lo, hi in ranges:
+        exp = oracle_range(spec, dt, oracle_cfg(w, max_grad_norm=1.0), lo, hi, sumsq=osumsq)
+        worst = compare_state(exp, device_range(p, m, v, lp, lo, hi), dt, f"2^32+ [{lo},{hi}) ")
+    _copy_matches_cast_everywhere(p, lp, dt)
+    progress(f"2^32+: norm {norm:.4f} (clip active), {len(ranges)} ranges verified; last: {worst}")
+
+
 def test_c3_loss_scaled_fp16_2e9_overflow_then_clip():
     w = zi_synth.workload("c3")
     n, dt, spec = w["numel"][0], w["lp_dtype"], w["spec"]
