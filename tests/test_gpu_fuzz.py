@@ -134,3 +134,85 @@ def test_forty_consecutive_steps_follow_the_oracle(dt, loss_scale, g_std):
             rep = compare_state((p, m, v, lp), (to_np(dp), to_np(dm), to_np(dv), to_np(dlp)), dt, f"iteration {it} ")
             progress(f"trajectory dt={dt} iteration {it} (step {step}): {rep}")
     assert step == 39
+
+
+def _host_array(a, where):
+    """A copy of `a` in pinned ("pin"), ordinary ("page") or device ("dev") memory; (holder, numpy view or None)."""
+    if where == "dev":
+        return to_dev(a), None
+    if where == "pin":
+        t = torch.empty(max(a.size, 1), dtype=torch.float32 if a.dtype == np.float32 else torch.int16, pin_memory=True)
+        view = t.numpy()[:a.size]
+        view[:] = a if a.dtype == np.float32 else a.view(np.int16)
+        return t, view
+    c = a.copy()
+    return c, c
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_streamed_lists(seed):
+    """The streamed step on drawn lists: 1-120 tensors from empty to several chunks long, chunk size and
+    slot count drawn too, state pinned or ordinary (ring), gradients / copy on the device or in host
+    memory, with or without a norm result.  Compared with the oracle element by element."""
+    rng = np.random.default_rng(0x5EA0 + seed)
+    dt = int(rng.choice([zi.ZI_BF16, zi.ZI_FP16]))
+    chunk_elems = int(rng.choice([1024, 4096, 16384]))
+    n_slots = int(rng.integers(2, 6))
+    n_tensors = int(rng.choice([1, 2, 5, 40, 120]))
+    kinds = [0, 1, int(rng.integers(2, 200)), int(rng.integers(200, chunk_elems)), chunk_elems,
+             int(rng.integers(chunk_elems + 1, 4 * chunk_elems))]
+    weights = [0.05, 0.1, 0.35, 0.3, 0.05, 0.15]
+    sizes = [int(kinds[k]) for k in rng.choice(len(kinds), n_tensors, p=weights)]
+    state_where = str(rng.choice(["pin", "page"]))
+    g_where = str(rng.choice(["dev", "pin", "page"]))
+    lp_where = str(rng.choice(["dev", "pin", "page", "none"]))
+    use_norm = bool(rng.random() < 0.7)
+    loss_scale = float(rng.choice([1.0, 1024.0]))
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, step=int(rng.choice([1, 10, 500])),
+              loss_scale=loss_scale, max_grad_norm=float(rng.choice([0.0, 0.5])),
+              mode=int(rng.choice([zi.ZI_MODE_ADAMW, zi.ZI_MODE_ADAM_L2])))
+    spec = zi_synth.StateSpec(0xBEE000 + seed, dt, g_std=1e-3 * loss_scale)
+    host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(sizes)]
+    exp = [(p.copy(), m.copy(), v.copy(), g, None if lp_where == "none" else np.zeros(p.size, np.uint16))
+           for (p, m, v, g) in host]
+    info = oracle.step(exp, dt, oracle.config(**hp), use_norm=use_norm)
+
+    needs_ring = "page" in (state_where, g_where, lp_where)
+    eng = zi.zi_engine_create(0, 4 * chunk_elems, n_slots)
+    try:
+        if needs_ring:
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_COPY_THREADS, int(rng.integers(1, 5)))
+            zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, int(rng.integers(2, 6)))
+        holders, tl = [], []
+        for (p, m, v, g) in host:
+            hs = [_host_array(a, state_where) for a in (p, m, v)]
+            hg = _host_array(g, g_where)
+            hl = (None, None) if lp_where == "none" else _host_array(np.zeros(p.size, np.uint16), lp_where)
+            holders.append((hs, hg, hl))
+            tl.append((hs[0][0], hs[1][0], hs[2][0], hg[0], hl[0], p.size))
+        nb = None
+        if use_norm:
+            nb = NormBuffers()
+            zi.zi_grad_norm_streamed(eng, tl, dt, loss_scale, nb.out, nb.ws)
+        st = zi.zi_adamw_step_streamed(eng, tl, dt, zi.make_config(**hp), None if nb is None else nb.out,
+                                       torch.cuda.current_stream())
+        assert st == zi.ZI_OK
+        if use_norm:
+            _, norm, flag = nb.read()
+            assert flag == info["found_inf"] == 0
+            assert abs(norm - info["norm"]) <= TOL_NORM_REL * max(info["norm"], 1e-300)
+        _, uses = zi.zi_plan_chunks(sizes, chunk_elems)
+        stats = zi.zi_engine_last_stats(eng)
+        per_elem = 12 + (2 if g_where != "dev" else 0)
+        assert stats.n_slot_uses == uses and stats.bytes_h2d == per_elem * sum(sizes)
+        rep = ""
+        for i, (e, (hs, hg, hl)) in enumerate(zip(exp, holders)):
+            got_lp = None
+            if lp_where != "none":
+                got_lp = to_np(hl[0]) if lp_where == "dev" else np.asarray(hl[1]).view(np.uint16).copy()
+            got = tuple(np.asarray(x[1]).copy() for x in hs) + (got_lp,)
+            rep = compare_state((e[0], e[1], e[2], e[4]), got, dt, f"seed {seed} tensor {i} (n={sizes[i]}) ")
+        progress(f"streamed fuzz seed {seed}: dt={dt} chunk={chunk_elems} slots={n_slots} tensors={n_tensors} "
+                 f"state={state_where} g={g_where} lp={lp_where} norm={use_norm}: {uses} slot uses; last {rep}")
+    finally:
+        zi.zi_engine_destroy(eng)
