@@ -118,6 +118,10 @@ inline int choose_head(const void* p, const void* m, const void* v, const void* 
     return best_h;
 }
 
+// Tensors of at least this many tiles (2^22 elements, some 20 microseconds of HBM time) are launched
+// alone; shorter ones share launches of up to kMaxStepDesc tensors.
+constexpr int64_t kSoloTiles = 8192;
+
 // Issues the fused step over a list of device-resident segments.
 struct StepIssuer {
     zi::StepArgs args{};
@@ -132,7 +136,14 @@ struct StepIssuer {
     {
         args.c = c;
         args.d_norm = d_norm;
+        reset();
+    }
+
+    void reset()
+    {
         args.n_desc = 0;
+        tiles = 0;
+        for (uint32_t& f : args.first_tile) f = 0xFFFFFFFFu;
     }
 
     hipError_t flush()
@@ -142,8 +153,7 @@ struct StepIssuer {
             e = zi::launch_step_wide(args, tiles, dt, l2, stream);
             ++launches;
         }
-        args.n_desc = 0;
-        tiles = 0;
+        reset();
         return e;
     }
 
@@ -158,11 +168,24 @@ struct StepIssuer {
         int64_t nt = (nquad + zi::kStepTileQuads - 1) / zi::kStepTileQuads;
         if (nt < 1) nt = 1;                       // the first tile also owns the unaligned ends
         if (nt > 0x7FFFFFFF) return hipErrorInvalidValue;
+        if (nt >= kSoloTiles) {                   // a launch of its own: no tensor lookup in the kernel
+            zi::StepArgs solo{};
+            solo.c = args.c;
+            solo.d_norm = args.d_norm;
+            solo.n_desc = 1;
+            for (uint32_t& f : solo.first_tile) f = 0xFFFFFFFFu;
+            d.first_tile = 0;
+            solo.first_tile[0] = 0;
+            solo.t[0] = d;
+            ++launches;
+            return zi::launch_step_wide(solo, (uint32_t)nt, dt, l2, stream);
+        }
         if (args.n_desc == zi::kMaxStepDesc || (uint64_t)tiles + (uint64_t)nt > 0x7FFFFFFFull) {
             hipError_t e = flush();
             if (e != hipSuccess) return e;
         }
         d.first_tile = tiles;
+        args.first_tile[args.n_desc] = tiles;
         args.t[args.n_desc++] = d;
         tiles += (uint32_t)nt;
         return hipSuccess;
@@ -216,7 +239,12 @@ struct NormIssuer {
     {
         a.partials = partials;
         a.partial_base = 0;
+        clear_table();
+    }
+    void clear_table()
+    {
         a.n_desc = 0;
+        for (uint32_t& f : a.first_block) f = 0xFFFFFFFFu;
     }
     hipError_t flush_launch()
     {
@@ -224,7 +252,7 @@ struct NormIssuer {
         if (a.n_desc > 0) e = zi::launch_norm_partials(a, blocks, dt, s);
         used += blocks;
         a.partial_base = used;
-        a.n_desc = 0;
+        clear_table();
         blocks = 0;
         return e;
     }
@@ -254,6 +282,7 @@ struct NormIssuer {
         d.head = (int32_t)(h < n ? h : n);
         d.first_block = blocks;
         d.n_blocks = (uint32_t)nb;
+        a.first_block[a.n_desc] = blocks;
         a.t[a.n_desc++] = d;
         blocks += (uint32_t)nb;
         return hipSuccess;

@@ -74,6 +74,9 @@ struct StepArgs {
     int32_t n_desc;
     StepConsts c;
     const zi_norm_result* d_norm;   // device, may be null
+    // first_tile of every descriptor once more, packed, 0xFFFFFFFF beyond n_desc: a workgroup finds its
+    // tensor by counting the entries <= its id (a few wide scalar loads, no dependent chain).
+    uint32_t first_tile[kMaxStepDesc];
 };
 
 struct NormDesc {
@@ -87,6 +90,7 @@ struct NormDesc {
 
 struct NormArgs {
     NormDesc t[kMaxNormDesc];
+    uint32_t first_block[kMaxNormDesc];   // packed copy of the descriptors' first_block, 0xFFFFFFFF beyond n_desc
     int32_t n_desc;
     uint32_t partial_base;          // index of this launch's first partial
     NormPartial* partials;

@@ -206,21 +206,45 @@ __device__ __forceinline__ u32x2 step_quad(f32x4& p, f32x4& m, f32x4& v, const u
 
 // One workgroup = one tile of kStepTileElems elements of one tensor.  blockIdx.x counts tiles over
 // all tensors of the launch; first_tile locates the tensor.
-template <int DT, bool L2>
+// SINGLE: the launch covers one tensor (every long tensor gets such a launch: a workgroup lives for a few
+// microseconds, so even a short search for its tensor costs bandwidth).  Otherwise the workgroup counts
+// the table entries <= its id: a few wide scalar loads and no dependent chain.
+template <int DT, bool L2, bool SINGLE>
 __global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs a)
 {
     float gscale;
     if (!step_prologue(a.d_norm, a.c, gscale)) return;
 
-    uint32_t tile = blockIdx.x;
+    const uint32_t block = blockIdx.x;
     int d = 0;
-    while (d + 1 < a.n_desc && tile >= a.t[d + 1].first_tile) ++d;
+    if constexpr (!SINGLE) {
+        d = -1;                           // first_tile[0] is 0, so the count is at least 1
+#pragma unroll
+        for (int i = 0; i < kMaxStepDesc; ++i) d += block >= a.first_tile[i] ? 1 : 0;
+    }
     const StepDesc& T = a.t[d];
-    tile -= T.first_tile;
 
     const int64_t head = T.head;
     const int64_t nquad = (T.numel - head) / kQuad;        // whole quads of the aligned body
     const int64_t body_end = head + nquad * kQuad;
+
+    // XCD-aware renumbering.  Workgroup ids of the launch go round-robin to the XCDs, so the runs are
+    // counted in launch-wide ids (a tensor that does not start on a run boundary keeps the XCD <->
+    // contiguous-tiles correspondence); it is a bijection on every run of 8 * kStepXcdRun workgroups
+    // that lies inside one tensor, and the workgroups of incomplete runs keep their tiles.
+    int64_t ti;
+    {
+        constexpr uint32_t run = kXcds * kStepXcdRun;
+        int64_t ntiles = (nquad + kStepTileQuads - 1) / kStepTileQuads;
+        if (ntiles < 1) ntiles = 1;
+        const uint32_t r = block % run;
+        const uint32_t base = block - r;
+        uint32_t nb = block;
+        if (base >= T.first_tile && (int64_t)(base - T.first_tile) + run <= ntiles)
+            nb = base + (r % kXcds) * (uint32_t)kStepXcdRun + r / kXcds;
+        ti = (int64_t)(nb - T.first_tile);
+    }
+    const int64_t tile = ti;
 
     // Elements before the vector body (at most 63) and after it (at most 3), by the tensor's first tile.
     if (tile == 0) {
@@ -236,17 +260,6 @@ __global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs
     const u32x2_mem* __restrict__ g2 = reinterpret_cast<const u32x2_mem*>(T.g + head);
     u32x2_mem* __restrict__ lp2 = T.p_lp ? reinterpret_cast<u32x2_mem*>(T.p_lp + head) : nullptr;
 
-    // XCD-aware renumbering (a bijection on the complete runs of 8 * kStepXcdRun tiles; the few
-    // tiles after the last complete run keep their numbers).
-    int64_t ti = tile;
-    {
-        constexpr int64_t run = kXcds * kStepXcdRun;
-        const int64_t ntiles = (nquad + kStepTileQuads - 1) / kStepTileQuads;
-        if (ti < ntiles / run * run) {
-            const int64_t r = ti % run;
-            ti = ti - r + (r % kXcds) * kStepXcdRun + r / kXcds;
-        }
-    }
     const int64_t q0 = ti * kStepTileQuads + threadIdx.x;
 
     if ((ti + 1) * kStepTileQuads <= nquad) {
@@ -290,13 +303,17 @@ hipError_t launch_step_wide(const StepArgs& a, uint32_t n_tiles, int dt, bool l2
 {
     if (n_tiles == 0) return hipSuccess;
     const dim3 grid(n_tiles), block(kStepThreads);
+    const bool single = a.n_desc == 1;
+#define ZI_LAUNCH_STEP(DT, L2, SINGLE) \
+    hipLaunchKernelGGL((adamw_wide_kernel<DT, L2, SINGLE>), grid, block, kStepOccupancyLds, s, a)
     if (dt == ZI_BF16) {
-        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, true>), grid, block, kStepOccupancyLds, s, a);
-        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_BF16, false>), grid, block, kStepOccupancyLds, s, a);
+        if (l2) { if (single) ZI_LAUNCH_STEP(ZI_BF16, true, true); else ZI_LAUNCH_STEP(ZI_BF16, true, false); }
+        else    { if (single) ZI_LAUNCH_STEP(ZI_BF16, false, true); else ZI_LAUNCH_STEP(ZI_BF16, false, false); }
     } else {
-        if (l2) hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, true>), grid, block, kStepOccupancyLds, s, a);
-        else    hipLaunchKernelGGL((adamw_wide_kernel<ZI_FP16, false>), grid, block, kStepOccupancyLds, s, a);
+        if (l2) { if (single) ZI_LAUNCH_STEP(ZI_FP16, true, true); else ZI_LAUNCH_STEP(ZI_FP16, true, false); }
+        else    { if (single) ZI_LAUNCH_STEP(ZI_FP16, false, true); else ZI_LAUNCH_STEP(ZI_FP16, false, false); }
     }
+#undef ZI_LAUNCH_STEP
     return hipGetLastError();
 }
 
@@ -379,8 +396,9 @@ template <int DT>
 __global__ __launch_bounds__(kThreads) void sumsq_partial_kernel(const NormArgs a)
 {
     uint32_t b = blockIdx.x;
-    int d = 0;
-    while (d + 1 < a.n_desc && b >= a.t[d + 1].first_block) ++d;
+    int d = -1;                               // first_block[0] is 0: the count is at least 1
+#pragma unroll
+    for (int i = 0; i < kMaxNormDesc; ++i) d += b >= a.first_block[i] ? 1 : 0;
     const NormDesc& T = a.t[d];
     b -= T.first_block;
 
