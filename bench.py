@@ -134,8 +134,36 @@ def resident(args, torch, zi, zs):
             b.synchronize()
             ts.append(a.elapsed_time(b))
         ceil[name + "_GBps"] = round(moved / (sorted(ts)[len(ts) // 2] * 1e-3) / 1e9, 1)
+    # A ragged tensor list carved from the same buffers (one transformer layer at hidden size 8192: four
+    # matrices of 67M-268M elements and eight vectors of 8K-32K), beside one flat tensor of the same length.
+    tensor_list = None
+    shapes = [k for _, k in zs.transformer_layer_shapes(8192)]
+    if sum(shapes) <= n:
+        def timed_step(items):
+            t_l = zi.make_tensors(items)
+            ts = []
+            for _ in range(6):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                zi.zi_grad_norm(t_l, dt, w["loss_scale"], d_norm, ws, stream=stream)
+                a.record(stream)
+                zi.zi_adamw_step(t_l, dt, cfg, d_norm, stream=stream)
+                b.record(stream)
+                b.synchronize()
+                ts.append(a.elapsed_time(b))
+            return sorted(ts[1:])[len(ts[1:]) // 2]
+        items, o = [], 0
+        for k in shapes:
+            items.append((p[o:o + k], m[o:o + k], v[o:o + k], g[o:o + k], lp[o:o + k], k))
+            o += k
+        ms_list = timed_step(items)
+        ms_flat = timed_step([(p[:o], m[:o], v[:o], g[:o], lp[:o], o)])
+        tensor_list = dict(what=f"fused step over a list of {len(shapes)} tensors ({o} elements: one transformer layer "
+                                "at hidden size 8192), beside one flat tensor of the same length",
+                           list_GBps=round(BYTES_PER_ELEM_STEP * o / (ms_list * 1e-3) / 1e9, 1),
+                           flat_GBps=round(BYTES_PER_ELEM_STEP * o / (ms_flat * 1e-3) / 1e9, 1),
+                           list_over_flat=round(ms_flat / ms_list, 4))
     out = dict(
-        n=n, sec_per_step=sec_per_step,
+        n=n, sec_per_step=sec_per_step, tensor_list=tensor_list,
         roofline=dict(bound="hbm", kernel="adamw_wide_kernel", achieved=round(achieved, 1), peak=HBM_PEAK_GBS,
                       unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
                       bytes_per_launch=BYTES_PER_ELEM_STEP * n, kernel_ms=round(k_ms, 4)),
@@ -375,7 +403,7 @@ def main():
 
     res = resident(args, torch, zi, zs)
     extras = dict(update_only_params_per_s=res["update_only_params_per_s"], norm=res["norm"],
-                  hbm_ceilings=res["hbm_ceilings"])
+                  hbm_ceilings=res["hbm_ceilings"], tensor_list=res["tensor_list"])
     if not args.no_streamed:
         extras["streamed"] = streamed(args, torch, zi, zs)
     line = {
