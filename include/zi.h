@@ -333,6 +333,26 @@ zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_
                          int64_t cap, int64_t* n_segments_out, int64_t* n_slot_uses_out);
 
 /*
+ * Launch plan of zi_adamw_step, as a pure host function (no GPU needed; nothing is dereferenced, only
+ * the addresses and lengths of t[] are used).  One item per non-empty tensor: the number of leading
+ * elements handled one by one before the 4-element lane vectors start (0..63, chosen so that as much
+ * of the tensor's traffic as possible starts on 128-byte lines), its tiles of 512 elements, and the
+ * launch it belongs to.  Tensors of 2^22 elements or more get a launch of their own (`alone`);
+ * shorter ones share launches of up to 32 tensors.  Writes at most `cap` items and always the totals.
+ */
+typedef struct {
+    int32_t tensor;        /* index into t[] */
+    int32_t head;          /* leading elements handled one by one */
+    int64_t n_tiles;
+    int64_t first_tile;    /* first workgroup of this tensor within its launch */
+    int32_t launch;        /* 0-based, in issue order */
+    int32_t alone;         /* 1 if the launch holds this tensor only */
+} zi_step_plan_item;
+
+zi_status zi_plan_step(const zi_tensor* t, int32_t n_tensors, zi_step_plan_item* out, int64_t cap,
+                       int64_t* n_items_out, int64_t* n_launches_out);
+
+/*
  * The step on the host CPUs, for state, gradients and copy that all live in HOST memory (any host
  * memory).  This is the paper's own placement of the offloaded step (Section 5.2.2: with optimizer
  * states in CPU memory the step uses the CPUs' aggregate compute and memory bandwidth; only 2 bytes

@@ -6,4 +6,4 @@ include/zi.h).  PyTorch is used by callers for device memory and streams only.
 from .binding import *  # noqa: F401,F403
 from .binding import (EXPORTS, LIB_PATH, ZiError, lib, make_config, make_file_tensors, make_tensors,
                       zi_adamw_config, zi_file_tensor,
-                      zi_chunk_segment, zi_norm_result, zi_stream_stats, zi_tensor)
+                      zi_chunk_segment, zi_norm_result, zi_step_plan_item, zi_stream_stats, zi_tensor)

@@ -34,7 +34,7 @@ EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
     "zi_grad_norm_streamed", "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
-    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh",
+    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh", "zi_plan_step",
 ]
 
 
@@ -77,6 +77,11 @@ class zi_stream_stats(ctypes.Structure):
 class zi_chunk_segment(ctypes.Structure):
     _fields_ = [("tensor", ctypes.c_int32), ("reserved", ctypes.c_int32), ("elem_offset", ctypes.c_int64),
                 ("count", ctypes.c_int64), ("slot_use", ctypes.c_int64), ("slot_offset", ctypes.c_int64)]
+
+
+class zi_step_plan_item(ctypes.Structure):
+    _fields_ = [("tensor", ctypes.c_int32), ("head", ctypes.c_int32), ("n_tiles", ctypes.c_int64),
+                ("first_tile", ctypes.c_int64), ("launch", ctypes.c_int32), ("alone", ctypes.c_int32)]
 
 
 _lib = None
@@ -125,6 +130,9 @@ def lib() -> ctypes.CDLL:
         L.zi_plan_chunks.restype = ctypes.c_int
         L.zi_plan_chunks.argtypes = [ctypes.POINTER(i64), i32, i64, ctypes.POINTER(zi_chunk_segment), i64,
                                      ctypes.POINTER(i64), ctypes.POINTER(i64)]
+        L.zi_plan_step.restype = ctypes.c_int
+        L.zi_plan_step.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.POINTER(zi_step_plan_item), i64,
+                                   ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.zi_host_grad_norm.restype = ctypes.c_int
         L.zi_host_grad_norm.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int, ctypes.c_float,
                                         ctypes.POINTER(zi_norm_result), i32]
@@ -299,6 +307,17 @@ def zi_plan_chunks(numel: Sequence[int], chunk_elems: int):
     out = (zi_chunk_segment * max(nseg.value, 1))()
     _check(lib().zi_plan_chunks(arr, n, int(chunk_elems), out, nseg.value, ctypes.byref(nseg), ctypes.byref(nuse)))
     return [out[i] for i in range(nseg.value)], nuse.value
+
+
+def zi_plan_step(tensors):
+    """(items, n_launches): how zi_adamw_step would launch the list; items are zi_step_plan_item records.
+    Tensors may be given by plain integer addresses: nothing is dereferenced."""
+    arr, n = _as_tensor_array(tensors)
+    nitems, nlaunch = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().zi_plan_step(arr, n, None, 0, ctypes.byref(nitems), ctypes.byref(nlaunch)))
+    out = (zi_step_plan_item * max(nitems.value, 1))()
+    _check(lib().zi_plan_step(arr, n, out, nitems.value, ctypes.byref(nitems), ctypes.byref(nlaunch)))
+    return [out[i] for i in range(nitems.value)], nlaunch.value
 
 
 def zi_host_grad_norm(tensors, dt: int, loss_scale: float, n_threads: int = 1) -> zi_norm_result:

@@ -4,6 +4,8 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <new>
+#include <vector>
 
 #include "zi_host.h"
 
@@ -79,6 +81,31 @@ extern "C" zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_
         ZI_HIP(issue.add((float*)t[i].p, (float*)t[i].m, (float*)t[i].v, (const uint16_t*)t[i].g,
                          (uint16_t*)t[i].p_lp, t[i].numel));
     ZI_HIP(issue.flush());
+    return ZI_OK;
+}
+
+extern "C" zi_status zi_plan_step(const zi_tensor* t, int32_t n_tensors, zi_step_plan_item* out, int64_t cap,
+                                  int64_t* n_items_out, int64_t* n_launches_out)
+{
+    if (zi_status st = check_step_tensors(t, n_tensors)) return st;
+    if (cap < 0 || (cap > 0 && !out)) return fail(ZI_ERR_INVALID_ARG, "bad output buffer");
+    if (!n_items_out || !n_launches_out) return fail(ZI_ERR_INVALID_ARG, "output counters are NULL");
+    std::vector<zi_step_plan_item> items;
+    try {
+        StepIssuer issue(zi::StepConsts{}, nullptr, ZI_BF16, false, nullptr);
+        issue.plan = &items;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            issue.cur_tensor = i;
+            (void)issue.add((float*)t[i].p, (float*)t[i].m, (float*)t[i].v, (const uint16_t*)t[i].g,
+                            (uint16_t*)t[i].p_lp, t[i].numel);
+        }
+        (void)issue.flush();
+        *n_launches_out = issue.launches;
+    } catch (const std::bad_alloc&) {
+        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+    }
+    for (int64_t i = 0; i < (int64_t)items.size() && i < cap; ++i) out[i] = items[(size_t)i];
+    *n_items_out = (int64_t)items.size();
     return ZI_OK;
 }
 

@@ -130,6 +130,11 @@ struct StepIssuer {
     bool l2;
     hipStream_t stream;
     int64_t launches = 0;
+    // Planning mode (zi_plan_step): with a sink set nothing is launched; every descriptor of every
+    // launch is recorded instead.  `cur_tensor` is the caller's index of the tensor being added.
+    std::vector<zi_step_plan_item>* plan = nullptr;
+    int32_t cur_tensor = -1;
+    int32_t tensor_of[zi::kMaxStepDesc] = {};
 
     StepIssuer(const zi::StepConsts& c, const zi_norm_result* d_norm, int dt_, bool l2_, hipStream_t s)
         : dt(dt_), l2(l2_), stream(s)
@@ -146,13 +151,22 @@ struct StepIssuer {
         for (uint32_t& f : args.first_tile) f = 0xFFFFFFFFu;
     }
 
+    hipError_t launch(const zi::StepArgs& a, uint32_t n_tiles, const int32_t* tensors)
+    {
+        const int64_t index = launches++;
+        if (!plan) return zi::launch_step_wide(a, n_tiles, dt, l2, stream);
+        for (int32_t i = 0; i < a.n_desc; ++i) {
+            const int64_t end = i + 1 < a.n_desc ? a.t[i + 1].first_tile : n_tiles;
+            plan->push_back({tensors[i], a.t[i].head, end - (int64_t)a.t[i].first_tile, (int64_t)a.t[i].first_tile,
+                             (int32_t)index, a.n_desc == 1 ? 1 : 0});
+        }
+        return hipSuccess;
+    }
+
     hipError_t flush()
     {
         hipError_t e = hipSuccess;
-        if (args.n_desc > 0) {
-            e = zi::launch_step_wide(args, tiles, dt, l2, stream);
-            ++launches;
-        }
+        if (args.n_desc > 0) e = launch(args, tiles, tensor_of);
         reset();
         return e;
     }
@@ -177,8 +191,7 @@ struct StepIssuer {
             d.first_tile = 0;
             solo.first_tile[0] = 0;
             solo.t[0] = d;
-            ++launches;
-            return zi::launch_step_wide(solo, (uint32_t)nt, dt, l2, stream);
+            return launch(solo, (uint32_t)nt, &cur_tensor);
         }
         if (args.n_desc == zi::kMaxStepDesc || (uint64_t)tiles + (uint64_t)nt > 0x7FFFFFFFull) {
             hipError_t e = flush();
@@ -186,6 +199,7 @@ struct StepIssuer {
         }
         d.first_tile = tiles;
         args.first_tile[args.n_desc] = tiles;
+        tensor_of[args.n_desc] = cur_tensor;
         args.t[args.n_desc++] = d;
         tiles += (uint32_t)nt;
         return hipSuccess;
