@@ -210,7 +210,8 @@ __device__ __forceinline__ u32x2 step_quad(f32x4& p, f32x4& m, f32x4& v, const u
 // microseconds, so even a short search for its tensor costs bandwidth).  Otherwise the workgroup counts
 // the table entries <= its id: a few wide scalar loads and no dependent chain.
 template <int DT, bool L2, bool SINGLE>
-__global__ __launch_bounds__(kStepThreads) void adamw_wide_kernel(const StepArgs a)
+__global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(1, 2)))
+void adamw_wide_kernel(const StepArgs a)
 {
     float gscale;
     if (!step_prologue(a.d_norm, a.c, gscale)) return;
