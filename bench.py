@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--numel", type=int, default=0, help="override the element count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streamed", action="store_true")
+    ap.add_argument("--no-tensor-list", action="store_true", help="leave out the tensor-list figure (profiling runs)")
     ap.add_argument("--cpu-sample", type=int, default=1_300_000_000, help="elements the oracle is timed on")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (scales rocprofv3 byte counters)")
@@ -138,7 +139,7 @@ def resident(args, torch, zi, zs):
     # matrices of 67M-268M elements and eight vectors of 8K-32K), beside one flat tensor of the same length.
     tensor_list = None
     shapes = [k for _, k in zs.transformer_layer_shapes(8192)]
-    if sum(shapes) <= n:
+    if sum(shapes) <= n and not args.no_tensor_list:
         def timed_step(items):
             t_l = zi.make_tensors(items)
             ts = []
