@@ -63,6 +63,9 @@
  *     of its traffic runs in whole 128-byte lines.  Other placements use the
  *     same kernel and give identical results, within a few percent of that
  *     speed.
+ *   - Every array a kernel will touch is checked at its first and last byte before anything is launched:
+ *     it must be device or page-locked host memory (both reachable by the GPU).  An ordinary host
+ *     pointer is ZI_ERR_INVALID_ARG, never a GPU memory fault.
  *   - numel == 0 and n_tensors == 0 are valid and do nothing.
  *   - Threads: calls that do not share buffers or an engine may run concurrently from different
  *     threads.  An engine serves one call at a time.  zi_last_error() is per thread.

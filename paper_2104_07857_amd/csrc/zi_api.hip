@@ -48,6 +48,10 @@ extern "C" zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_d
                                   void* hip_stream)
 {
     if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, d_workspace, workspace_bytes)) return st;
+    if (zi_status st = check_kernel_visible(d_out, sizeof(zi_norm_result), -1, "d_out")) return st;
+    if (zi_status st = check_kernel_visible(d_workspace, workspace_bytes, -1, "d_workspace")) return st;
+    for (int32_t i = 0; i < n_tensors; ++i)
+        if (zi_status st = check_kernel_visible(t[i].g, (size_t)t[i].numel * 2, i, "g")) return st;
 
     NormIssuer issue((zi::NormPartial*)d_workspace, (int)dt, loss_scale, d_out, (hipStream_t)hip_stream);
     for (int32_t i = 0; i < n_tensors; ++i) ZI_HIP(issue.add((const uint16_t*)t[i].g, t[i].numel));
@@ -59,6 +63,7 @@ extern "C" zi_status zi_norm_refresh(zi_norm_result* d_result, float loss_scale,
 {
     if (!d_result) return fail(ZI_ERR_INVALID_ARG, "d_result is NULL");
     if (!aligned(d_result, 8)) return fail(ZI_ERR_ALIGNMENT, "d_result must be 8-byte aligned");
+    if (zi_status st = check_kernel_visible(d_result, sizeof(zi_norm_result), -1, "d_result")) return st;
     if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
         return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
     ZI_HIP(zi::launch_norm_refresh(d_result, loss_scale, (hipStream_t)hip_stream));
@@ -74,6 +79,15 @@ extern "C" zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_
     if (zi_status st = check_config(cfg)) return st;
     if (zi_status st = check_step_tensors(t, n_tensors)) return st;
     if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
+    if (zi_status st = check_kernel_visible(d_norm, sizeof(zi_norm_result), -1, "d_norm")) return st;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        const size_t n = (size_t)t[i].numel;
+        if (zi_status st = check_kernel_visible(t[i].p, n * 4, i, "p")) return st;
+        if (zi_status st = check_kernel_visible(t[i].m, n * 4, i, "m")) return st;
+        if (zi_status st = check_kernel_visible(t[i].v, n * 4, i, "v")) return st;
+        if (zi_status st = check_kernel_visible(t[i].g, n * 2, i, "g")) return st;
+        if (zi_status st = check_kernel_visible(t[i].p_lp, n * 2, i, "p_lp")) return st;
+    }
 
     const zi::StepConsts k = make_consts(*cfg);
     StepIssuer issue(k, d_norm, (int)dt, cfg->mode == ZI_MODE_ADAM_L2, (hipStream_t)hip_stream);
@@ -119,6 +133,9 @@ extern "C" zi_status zi_hbm_probe(void* d_a, void* d_b, size_t bytes, int32_t mo
     if (bytes < 16 || bytes % 16) return fail(ZI_ERR_INVALID_ARG, "bytes must be a positive multiple of 16");
     if (bytes / 16 / zi::kThreads > 0x7FFFFFFFull) return fail(ZI_ERR_INVALID_ARG, "bytes too large for one launch");
     if (!aligned(d_a, 16) || !aligned(d_b, 16)) return fail(ZI_ERR_ALIGNMENT, "buffers must be 16-byte aligned");
+    if (zi_status st = check_kernel_visible(d_a, bytes, -1, "d_a")) return st;
+    if (mode == 1)
+        if (zi_status st = check_kernel_visible(d_b, bytes, -1, "d_b")) return st;
     // mode 0 needs a place for a store that never happens: the first float of d_a itself
     ZI_HIP(zi::launch_hbm_probe(d_a, d_b, (int64_t)(bytes / 16), mode, (float*)d_a, (hipStream_t)hip_stream));
     return ZI_OK;

@@ -280,21 +280,6 @@ struct StateSrc {
     int64_t numel;
 };
 
-// Device, page-locked host or ordinary host memory?  (0, 1, 2; -1 for anything else.)
-int memory_kind(const void* p)
-{
-    hipPointerAttribute_t attr{};
-    const hipError_t pe = hipPointerGetAttributes(&attr, p);
-    if (pe != hipSuccess) {
-        (void)hipGetLastError();
-        return 2;
-    }
-    if (attr.type == hipMemoryTypeDevice) return 0;
-    if (attr.type == hipMemoryTypeHost) return 1;
-    if (attr.type == hipMemoryTypeUnregistered) return 2;
-    return -1;
-}
-
 // After a failed call: wait for whatever the engine's streams still hold, keeping the first error.
 void drain_streams(zi_engine* e)
 {
@@ -625,6 +610,7 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
     if (zi_status st = check_config(cfg)) return st;
     if (zi_status st = check_step_tensors(t, n_tensors)) return st;
     if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
+    if (zi_status st = check_kernel_visible(d_norm, sizeof(zi_norm_result), -1, "d_norm")) return st;
 
     ZI_HIP(hipSetDevice(e->device));
     hipStream_t user = (hipStream_t)hip_stream;
@@ -677,6 +663,8 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
 {
     if (zi_status st = check_engine(e)) return st;
     if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, d_workspace, workspace_bytes)) return st;
+    if (zi_status st = check_kernel_visible(d_out, sizeof(zi_norm_result), -1, "d_out")) return st;
+    if (zi_status st = check_kernel_visible(d_workspace, workspace_bytes, -1, "d_workspace")) return st;
     ZI_HIP(hipSetDevice(e->device));
     hipStream_t user = (hipStream_t)hip_stream;
     e->stats = zi_stream_stats{};
@@ -838,6 +826,7 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
     if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
     if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
     if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
+    if (zi_status st = check_kernel_visible(d_norm, sizeof(zi_norm_result), -1, "d_norm")) return st;
     if (e->n_hslots == 0)
         return fail(ZI_ERR_INVALID_ARG, "file-resident state needs a pinned ring (ZI_OPT_HOST_RING_SLOTS)");
 

@@ -29,6 +29,38 @@ const char* last_error();
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// What kind of memory an address is: 0 device, 1 page-locked host, 2 ordinary host, -1 anything else,
+// -2 if the HIP runtime cannot answer (no usable device).
+inline int memory_kind(const void* p)
+{
+    hipPointerAttribute_t attr{};
+    const hipError_t pe = hipPointerGetAttributes(&attr, p);
+    if (pe != hipSuccess) {
+        (void)hipGetLastError();
+        return pe == hipErrorInvalidValue ? 2 : -2;      // older runtimes report unregistered memory this way
+    }
+    if (attr.type == hipMemoryTypeDevice) return 0;
+    if (attr.type == hipMemoryTypeHost) return 1;
+    if (attr.type == hipMemoryTypeUnregistered) return 2;
+    return -1;
+}
+
+// A kernel is about to read or write `bytes` at p: both ends must be memory the GPU can reach (device
+// or page-locked host).  An ordinary host pointer here would be a GPU memory fault, not an error code.
+inline zi_status check_kernel_visible(const void* p, size_t bytes, int tensor, const char* name)
+{
+    if (!p || bytes == 0) return ZI_OK;
+    const void* ends[2] = {p, static_cast<const char*>(p) + bytes - 1};
+    for (const void* e : ends) {
+        const int k = memory_kind(e);
+        if (k == -2) return fail(ZI_ERR_HIP, "no usable HIP device (pointer query failed)");
+        if (k != 0 && k != 1)
+            return fail(ZI_ERR_INVALID_ARG, "tensor %d: %s (%zu bytes) is not device or page-locked host memory",
+                        tensor, name, bytes);
+    }
+    return ZI_OK;
+}
+
 inline zi_status check_dtype(int dt)
 {
     if (dt != ZI_BF16 && dt != ZI_FP16) return fail(ZI_ERR_INVALID_ARG, "unknown low-precision dtype %d", dt);

@@ -282,3 +282,34 @@ def test_device_reproduces_the_oracle_golden_file():
         torch.cuda.synchronize()
         compare_state((c["out_p"], c["out_m"], c["out_v"], c["out_lp"]), (to_np(p), to_np(m), to_np(v), to_np(lp)),
                       c["dtype"], c["name"] + " ")
+
+
+def test_ordinary_host_pointers_are_refused_not_dereferenced():
+    """A pointer the GPU cannot reach is an argument error before any launch (page-locked host memory is fine)."""
+    n = 1000
+    w = zi_synth.workload("c1")
+    p, m, v, g = gen_numpy(w["spec"], n)
+    dp, dm, dv, dg = (to_dev(a) for a in (p, m, v, g))
+    dlp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    good = [dp, dm, dv, dg, dlp]
+    host = [p, m, v, g, np.zeros(n, np.uint16)]
+    for k in range(5):
+        args = list(good)
+        args[k] = host[k]
+        with pytest.raises(zi.ZiError) as ei:
+            zi.zi_adamw_step([tuple(args) + (n,)], zi.ZI_BF16, zi_cfg(w))
+        assert ei.value.status == zi.ZI_ERR_INVALID_ARG
+    nb = NormBuffers()
+    with pytest.raises(zi.ZiError):
+        zi.zi_grad_norm([(None, None, None, g, None, n)], zi.ZI_BF16, 1.0, nb.out, nb.ws)
+    with pytest.raises(zi.ZiError):
+        zi.zi_adamw_step([(dp, dm, dv, dg, dlp, n)], zi.ZI_BF16, zi_cfg(w), np.zeros(3, np.float64))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(dp), p)                       # nothing ran
+    # a tensor whose end lies beyond its allocation's registered range is caught at its last byte
+    pinned = torch.empty(n, dtype=torch.float32, pin_memory=True)
+    pinned.numpy()[:] = p
+    exp, _, _ = _run_both(p, m, v, g, zi.ZI_BF16, oracle_cfg(w), zi_cfg(w))
+    zi.zi_adamw_step([(pinned, dm, dv, dg, dlp, n)], zi.ZI_BF16, zi_cfg(w))      # page-locked host memory works
+    torch.cuda.synchronize()
+    assert np.array_equal(pinned.numpy().view(np.uint32), exp[0].view(np.uint32))
