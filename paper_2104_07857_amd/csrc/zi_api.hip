@@ -50,8 +50,9 @@ extern "C" zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_d
     if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, d_workspace, workspace_bytes)) return st;
     if (zi_status st = check_kernel_visible(d_out, sizeof(zi_norm_result), -1, "d_out")) return st;
     if (zi_status st = check_kernel_visible(d_workspace, workspace_bytes, -1, "d_workspace")) return st;
+    PointerChecker reach;
     for (int32_t i = 0; i < n_tensors; ++i)
-        if (zi_status st = check_kernel_visible(t[i].g, (size_t)t[i].numel * 2, i, "g")) return st;
+        if (zi_status st = reach.check(t[i].g, (size_t)t[i].numel * 2, i, "g")) return st;
 
     NormIssuer issue((zi::NormPartial*)d_workspace, (int)dt, loss_scale, d_out, (hipStream_t)hip_stream);
     for (int32_t i = 0; i < n_tensors; ++i) ZI_HIP(issue.add((const uint16_t*)t[i].g, t[i].numel));
@@ -80,13 +81,14 @@ extern "C" zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_
     if (zi_status st = check_step_tensors(t, n_tensors)) return st;
     if (d_norm && !aligned(d_norm, 8)) return fail(ZI_ERR_ALIGNMENT, "d_norm must be 8-byte aligned");
     if (zi_status st = check_kernel_visible(d_norm, sizeof(zi_norm_result), -1, "d_norm")) return st;
+    PointerChecker reach;
     for (int32_t i = 0; i < n_tensors; ++i) {
         const size_t n = (size_t)t[i].numel;
-        if (zi_status st = check_kernel_visible(t[i].p, n * 4, i, "p")) return st;
-        if (zi_status st = check_kernel_visible(t[i].m, n * 4, i, "m")) return st;
-        if (zi_status st = check_kernel_visible(t[i].v, n * 4, i, "v")) return st;
-        if (zi_status st = check_kernel_visible(t[i].g, n * 2, i, "g")) return st;
-        if (zi_status st = check_kernel_visible(t[i].p_lp, n * 2, i, "p_lp")) return st;
+        if (zi_status st = reach.check(t[i].p, n * 4, i, "p")) return st;
+        if (zi_status st = reach.check(t[i].m, n * 4, i, "m")) return st;
+        if (zi_status st = reach.check(t[i].v, n * 4, i, "v")) return st;
+        if (zi_status st = reach.check(t[i].g, n * 2, i, "g")) return st;
+        if (zi_status st = reach.check(t[i].p_lp, n * 2, i, "p_lp")) return st;
     }
 
     const zi::StepConsts k = make_consts(*cfg);

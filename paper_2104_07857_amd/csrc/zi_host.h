@@ -47,18 +47,47 @@ inline int memory_kind(const void* p)
 
 // A kernel is about to read or write `bytes` at p: both ends must be memory the GPU can reach (device
 // or page-locked host).  An ordinary host pointer here would be a GPU memory fault, not an error code.
+// Device allocations that have been looked up are remembered for the rest of the call, so a list of
+// thousands of views into a few allocations costs a few queries, not thousands.
+struct PointerChecker {
+    struct Range { uintptr_t lo, hi; };
+    Range known[8] = {};
+    int n_known = 0, next = 0;
+
+    zi_status check(const void* p, size_t bytes, int tensor, const char* name)
+    {
+        if (!p || bytes == 0) return ZI_OK;
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(p), hi = lo + bytes;
+        for (int i = 0; i < n_known; ++i)
+            if (lo >= known[i].lo && hi <= known[i].hi) return ZI_OK;
+        const void* ends[2] = {p, static_cast<const char*>(p) + bytes - 1};
+        for (const void* e : ends) {
+            const int k = memory_kind(e);
+            if (k == -2) return fail(ZI_ERR_HIP, "no usable HIP device (pointer query failed)");
+            if (k != 0 && k != 1)
+                return fail(ZI_ERR_INVALID_ARG, "tensor %d: %s (%zu bytes) is not device or page-locked host memory",
+                            tensor, name, bytes);
+        }
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) == hipSuccess && size > 0) {
+            const uintptr_t blo = reinterpret_cast<uintptr_t>(base);
+            if (lo >= blo && hi <= blo + size) {
+                known[next] = {blo, blo + size};
+                next = (next + 1) % 8;
+                if (n_known < 8) ++n_known;
+            }
+        } else {
+            (void)hipGetLastError();
+        }
+        return ZI_OK;
+    }
+};
+
 inline zi_status check_kernel_visible(const void* p, size_t bytes, int tensor, const char* name)
 {
-    if (!p || bytes == 0) return ZI_OK;
-    const void* ends[2] = {p, static_cast<const char*>(p) + bytes - 1};
-    for (const void* e : ends) {
-        const int k = memory_kind(e);
-        if (k == -2) return fail(ZI_ERR_HIP, "no usable HIP device (pointer query failed)");
-        if (k != 0 && k != 1)
-            return fail(ZI_ERR_INVALID_ARG, "tensor %d: %s (%zu bytes) is not device or page-locked host memory",
-                        tensor, name, bytes);
-    }
-    return ZI_OK;
+    PointerChecker c;
+    return c.check(p, bytes, tensor, name);
 }
 
 inline zi_status check_dtype(int dt)
