@@ -313,3 +313,26 @@ def test_ordinary_host_pointers_are_refused_not_dereferenced():
     zi.zi_adamw_step([(pinned, dm, dv, dg, dlp, n)], zi.ZI_BF16, zi_cfg(w))      # page-locked host memory works
     torch.cuda.synchronize()
     assert np.array_equal(pinned.numpy().view(np.uint32), exp[0].view(np.uint32))
+
+
+@pytest.mark.parametrize("dt", [zi.ZI_BF16, zi.ZI_FP16])
+def test_every_gradient_pattern(dt):
+    """All 65,536 bit patterns of a low-precision gradient (subnormals, both zeros, the largest finite
+    values; infinities and NaNs too: with no norm result nothing skips the step, NaN just propagates on
+    both sides), each met with three different states."""
+    w = zi_synth.workload("c1")
+    g = np.tile(np.arange(65536, dtype=np.uint32).astype(np.uint16), 3)
+    n = g.size
+    p, m, v, _ = gen_numpy(zi_synth.StateSpec(4242 + dt, dt), n)
+    m[65536:2 * 65536] = 0
+    v[65536:2 * 65536] = 0                                     # first-step state for the middle copy
+    ls = 1.0 if dt == zi.ZI_BF16 else 1024.0
+    exp, got, _ = _run_both(p, m, v, g, dt, oracle_cfg(w, loss_scale=ls), zi_cfg(w, loss_scale=ls))
+    special = np.isnan(exp[0])
+    assert special.sum() >= 3 * 2 * 3                          # the NaN / inf patterns did reach the arithmetic
+    for e, d in zip(exp[:3], got[:3]):
+        assert np.array_equal(np.isnan(e), np.isnan(d))
+    ok = ~special
+    rep = compare_state(tuple(a[ok] for a in exp[:3]) + (exp[3][ok],), tuple(a[ok] for a in got[:3]) + (got[3][ok],),
+                        dt, f"gradient patterns dt={dt} ")
+    progress(f"all gradient patterns dt={dt}: {rep}")
