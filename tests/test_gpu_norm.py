@@ -158,3 +158,21 @@ def test_two_slices_combined_like_two_ranks_give_the_global_clip():
         zi.zi_norm_refresh(None, 1.0)
     with pytest.raises(zi.ZiError):
         zi.zi_norm_refresh(r0.out, 0.0)
+
+
+@pytest.mark.parametrize("dt,expmask", [(zi.ZI_BF16, 0x7F80), (zi.ZI_FP16, 0x7C00)])
+def test_every_finite_pattern_is_squared_exactly(dt, expmask):
+    """All finite 16-bit patterns (subnormals, both zeros, the largest values: bf16 squares reach 1e77)
+    in one tensor: squares are exact in double and the sum agrees with the oracle's compensated sum."""
+    allp = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    finite = allp[(allp & expmask) != expmask]
+    rng = np.random.default_rng(3)
+    g = rng.permutation(np.tile(finite, 5))
+    want, flag0 = oracle.grad_sumsq([g], dt)
+    sumsq, _, flag = _gpu_norm([g], dt)
+    assert flag == flag0 == 0
+    assert math.isfinite(sumsq) and abs(sumsq - want) <= 1e-12 * want
+    # one non-finite pattern anywhere raises the flag
+    g2 = g.copy()
+    g2[12345] = expmask
+    assert _gpu_norm([g2], dt)[2] == 1
