@@ -149,6 +149,28 @@ zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, fl
                        zi_norm_result* d_out, void* d_workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * zi_grad_norm for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * same result struct, same kernels; the per-block partials go to a fixed array of
+ * ZI_NOALLOC_MAX_PARTIALS * 16 bytes (256 KiB) inside the library's device image, which every GPU the
+ * library runs on holds until the process ends.  The call itself allocates nothing, on the device or
+ * on the host.
+ * Limit: at most ZI_NOALLOC_MAX_PARTIALS non-empty tensors per call (ZI_ERR_UNSUPPORTED beyond,
+ * nothing launched); within it any sizes are accepted, long tensors simply get fewer workgroups so
+ * that all partials of the call fit the array in one pass.  The sum is accumulated in double in a
+ * different grouping than zi_grad_norm's when that happens (agreement ~1e-15 relative), and is
+ * bit-identical otherwise.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on the same GPU (different
+ * streams or threads) race on it and give garbage; order them on one stream or with events.  Nothing in
+ * the array needs clearing between calls: every partial the final pass reads was written by this call.
+ * The device address of the array is looked up on the first call on each device (that first call must
+ * not be under capture).  Asynchronous on hip_stream.
+ */
+#define ZI_NOALLOC_MAX_PARTIALS 16384
+zi_status zi_grad_norm_noalloc(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
+                               zi_norm_result* d_out, void* hip_stream);
+
+/*
  * Hook for a sharded run (Section 2, "ZeRO": every data-parallel process owns a slice of each
  * parameter and steps only that slice; the clip factor needs the norm over ALL slices).  Each rank
  * calls zi_grad_norm on its slice; the caller then combines the results across ranks, in place in

@@ -29,12 +29,13 @@ ZI_OPT_SKIP_KERNEL = 0
 ZI_OPT_HOST_RING_SLOTS = 1
 ZI_OPT_HOST_COPY_THREADS = 2
 ZI_OPT_MAX_INFLIGHT = 3
+ZI_NOALLOC_MAX_PARTIALS = 16384
 
 EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
     "zi_grad_norm_streamed", "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
-    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh", "zi_plan_step",
+    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh", "zi_plan_step", "zi_grad_norm_noalloc",
 ]
 
 
@@ -103,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.zi_norm_workspace_bytes.argtypes = [i64, i32]
         L.zi_grad_norm.restype = ctypes.c_int
         L.zi_grad_norm.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int, ctypes.c_float, vp, vp, sz, vp]
+        L.zi_grad_norm_noalloc.restype = ctypes.c_int
+        L.zi_grad_norm_noalloc.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int, ctypes.c_float, vp, vp]
         L.zi_adamw_step.restype = ctypes.c_int
         L.zi_adamw_step.argtypes = [ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
                                     ctypes.POINTER(zi_adamw_config), vp, vp]
@@ -224,6 +227,11 @@ def zi_grad_norm(tensors, dt: int, loss_scale: float, d_out, d_workspace, worksp
         workspace_bytes = d_workspace.numel() * d_workspace.element_size()
     return _check(lib().zi_grad_norm(arr, n, int(dt), float(loss_scale), _addr(d_out), _addr(d_workspace),
                                      int(workspace_bytes), _stream(stream)))
+
+
+def zi_grad_norm_noalloc(tensors, dt: int, loss_scale: float, d_out, stream=None) -> int:
+    arr, n = _as_tensor_array(tensors)
+    return _check(lib().zi_grad_norm_noalloc(arr, n, int(dt), float(loss_scale), _addr(d_out), _stream(stream)))
 
 
 def zi_adamw_step(tensors, dt: int, cfg: zi_adamw_config, d_norm=None, stream=None) -> int:

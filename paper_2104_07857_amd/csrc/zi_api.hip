@@ -4,6 +4,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -57,6 +58,79 @@ extern "C" zi_status zi_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_d
     NormIssuer issue((zi::NormPartial*)d_workspace, (int)dt, loss_scale, d_out, (hipStream_t)hip_stream);
     for (int32_t i = 0; i < n_tensors; ++i) ZI_HIP(issue.add((const uint16_t*)t[i].g, t[i].numel));
     ZI_HIP(issue.finish());   // also writes zeros for an empty list
+    return ZI_OK;
+}
+
+// ------------------------------------------------------------ grad norm without a workspace
+//
+// For callers that cannot allocate (code under graph capture, tight serving loops, harnesses that
+// forbid it): the per-block partials live in a fixed array in the device image of this library
+// instead of a caller-provided workspace.  Each GPU holds its own copy at its own address; the name
+// below is only a host-side stand-in, so the device address is looked up once per device and that
+// pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[ZI_NOALLOC_MAX_PARTIALS * sizeof(zi::NormPartial)];
+
+namespace {
+
+constexpr int kMaxScratchDevices = 64;
+std::mutex g_scratch_mu;
+zi::NormPartial* g_scratch_ptr[kMaxScratchDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+zi_status scratch_for_current_device(zi::NormPartial** out)
+{
+    int dev = -1;
+    ZI_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxScratchDevices)
+        return fail(ZI_ERR_UNSUPPORTED, "device ordinal %d is beyond the %d this call keeps scratch pointers for", dev,
+                    kMaxScratchDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        ZI_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(ZI_ERR_HIP, "hipGetSymbolAddress gave a null address for the scratch array");
+        g_scratch_ptr[dev] = static_cast<zi::NormPartial*>(ptr);
+    }
+    *out = g_scratch_ptr[dev];
+    return ZI_OK;
+}
+
+}  // namespace
+
+extern "C" zi_status zi_grad_norm_noalloc(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
+                                          zi_norm_result* d_out, void* hip_stream)
+{
+    static_assert(ZI_NOALLOC_MAX_PARTIALS <= zi::kMaxPartials, "the issuer counts partials against kMaxPartials");
+    zi::NormPartial* partials = nullptr;
+    if (zi_status st = scratch_for_current_device(&partials)) return st;
+    if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, partials,
+                                       sizeof(zi::NormPartial) * ZI_NOALLOC_MAX_PARTIALS))
+        return st;
+    if (zi_status st = check_kernel_visible(d_out, sizeof(zi_norm_result), -1, "d_out")) return st;
+    PointerChecker reach;
+    int64_t non_empty = 0;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (zi_status st = reach.check(t[i].g, (size_t)t[i].numel * 2, i, "g")) return st;
+        non_empty += t[i].numel > 0;
+    }
+    // One pass: every partial of the call must fit the fixed array.  Each tensor needs at least one
+    // workgroup, so the list length is the hard limit; below it, long tensors get fewer workgroups.
+    if (non_empty > ZI_NOALLOC_MAX_PARTIALS)
+        return fail(ZI_ERR_UNSUPPORTED, "%lld non-empty gradient tensors: the fixed scratch holds one partial for each of "
+                    "at most %d (split the list, or use zi_grad_norm with a workspace)", (long long)non_empty,
+                    ZI_NOALLOC_MAX_PARTIALS);
+    int64_t cap = NormIssuer::kBlocksPerTensor;
+    for (;; cap /= 2) {
+        int64_t total = 0;
+        for (int32_t i = 0; i < n_tensors; ++i)
+            if (t[i].numel > 0) total += NormIssuer::blocks_for(t[i].numel, cap);
+        if (total <= ZI_NOALLOC_MAX_PARTIALS || cap == 1) break;
+    }
+
+    NormIssuer issue(partials, (int)dt, loss_scale, d_out, (hipStream_t)hip_stream);
+    issue.blocks_cap = cap;
+    for (int32_t i = 0; i < n_tensors; ++i) ZI_HIP(issue.add((const uint16_t*)t[i].g, t[i].numel));
+    ZI_HIP(issue.finish());
     return ZI_OK;
 }
 

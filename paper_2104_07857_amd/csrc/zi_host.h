@@ -301,6 +301,7 @@ struct NormIssuer {
     static constexpr int64_t kBlocksPerTensor = 4096;
 
     zi::NormArgs a{};
+    int64_t blocks_cap = kBlocksPerTensor;   // workgroups one tensor may get (lowered by callers with a tight budget)
     uint32_t blocks = 0;       // blocks of the launch being assembled
     uint32_t used = 0;         // partials written since the last finalize
     int finalized = 0;
@@ -315,6 +316,11 @@ struct NormIssuer {
         a.partials = partials;
         a.partial_base = 0;
         clear_table();
+    }
+    static int64_t blocks_for(int64_t n, int64_t cap)
+    {
+        const int64_t nb = (n + kMinElemsPerBlock - 1) / kMinElemsPerBlock;
+        return nb > cap ? cap : nb;
     }
     void clear_table()
     {
@@ -342,8 +348,7 @@ struct NormIssuer {
     hipError_t add(const uint16_t* g, int64_t n)
     {
         if (n <= 0) return hipSuccess;
-        int64_t nb = (n + kMinElemsPerBlock - 1) / kMinElemsPerBlock;
-        if (nb > kBlocksPerTensor) nb = kBlocksPerTensor;
+        int64_t nb = blocks_for(n, blocks_cap);
         hipError_t e = hipSuccess;
         if (a.n_desc == zi::kMaxNormDesc && (e = flush_launch()) != hipSuccess) return e;
         if ((uint64_t)used + blocks + (uint64_t)nb > zi::kMaxPartials) {
