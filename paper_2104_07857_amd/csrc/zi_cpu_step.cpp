@@ -5,131 +5,159 @@
 // low-precision parameters go up over the link, 2 + 2 bytes per element instead of 12 + 12).  It is a
 // separate entry point that a caller chooses explicitly; no GPU entry point ever falls back to it.
 //
-// Same arithmetic, in the same binary32 order, as the HIP kernels (see include/zi.h), written with
-// AVX2 / FMA / F16C intrinsics: vector sqrt and divide are IEEE-correct, fmadd / fnmadd round once, and
-// the default MXCSR keeps denormals.  Compiled by the host compiler with -ffp-contract=off.
+// Same arithmetic, in the same binary32 order, as the HIP kernels (see include/zi.h).  There is ONE
+// arithmetic routine: eight lanes of AVX2 / FMA / F16C (vector sqrt and divide are IEEE-correct,
+// fmadd / fnmadd round once, the default MXCSR keeps denormals).  A range that is not a multiple of
+// eight ends in one more pass of the same routine over a padded group: the fp32 arrays are read and
+// written through lane masks, the 2-byte arrays through an 8-element stack copy, so no element is
+// ever computed by different code than its neighbours.  Compiled by the host compiler with
+// -ffp-contract=off.
 #include <immintrin.h>
 
 #include <algorithm>
 #include <atomic>
-#include <cmath>
-#include <cstdint>
 #include <cstring>
 #include <exception>
 #include <thread>
 #include <vector>
 
-#include "zi.h"
+#include "zi_checks.h"
 
-namespace zi {
-namespace host {
-zi_status fail(zi_status st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
-}
-}  // namespace zi
-
-using zi::host::fail;
+using namespace zi::host;
 
 namespace {
 
-struct Consts {
-    float beta1, beta2, omb1, omb2, eps, step_size, inv_sqrt_bc2, decay, weight_decay, gscale;
-    bool l2;
-};
-
-inline float widen_scalar(uint16_t h, int dt)
-{
-    if (dt == ZI_BF16) {
-        const uint32_t b = (uint32_t)h << 16;
-        float f;
-        std::memcpy(&f, &b, 4);
-        return f;
-    }
-    return _cvtsh_ss(h);
-}
-
-inline uint16_t narrow_scalar(float x, int dt)
-{
-    if (dt == ZI_BF16) {
-        uint32_t b;
-        std::memcpy(&b, &x, 4);
-        if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((b >> 16) | 0x0040u);
-        b += 0x7FFFu + ((b >> 16) & 1u);
-        return (uint16_t)(b >> 16);
-    }
-    return (uint16_t)_cvtss_sh(x, _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC);
-}
-
-inline void step_scalar(float* p, float* m, float* v, const uint16_t* g, uint16_t* lp, int64_t i, int dt,
-                        const Consts& c)
-{
-    float gi = widen_scalar(g[i], dt) * c.gscale;
-    if (c.l2) gi = std::fmaf(c.weight_decay, p[i], gi);
-    const float m1 = std::fmaf(c.beta1, m[i], c.omb1 * gi);
-    const float v1 = std::fmaf(c.beta2, v[i], c.omb2 * (gi * gi));
-    const float d = std::fmaf(std::sqrt(v1), c.inv_sqrt_bc2, c.eps);
-    const float q = m1 / d;
-    const float pd = std::fmaf(-c.decay, p[i], p[i]);
-    const float p1 = std::fmaf(-c.step_size, q, pd);
-    m[i] = m1;
-    v[i] = v1;
-    p[i] = p1;
-    if (lp) lp[i] = narrow_scalar(p1, dt);
-}
+// ------------------------------------------------------------------------------- 16-bit formats
 
 template <int DT>
-inline __m256 widen8(const uint16_t* g)
+inline __m256 widen8(__m128i h)
 {
-    const __m128i h = _mm_loadu_si128((const __m128i*)g);
     if (DT == ZI_BF16) return _mm256_castsi256_ps(_mm256_slli_epi32(_mm256_cvtepu16_epi32(h), 16));
     return _mm256_cvtph_ps(h);
 }
 
+// Eight fp32 values to eight 16-bit patterns, round to nearest even.
 template <int DT>
-inline void narrow8(__m256 x, uint16_t* out)
+inline __m128i narrow8(__m256 x)
 {
-    if (DT == ZI_FP16) {
-        _mm_storeu_si128((__m128i*)out, _mm256_cvtps_ph(x, _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC));
-        return;
-    }
-    // bf16, round to nearest even: add 0x7FFF + lsb, keep the upper half; NaN is quieted instead
-    const __m256i b = _mm256_castps_si256(x);
-    const __m256i lsb = _mm256_and_si256(_mm256_srli_epi32(b, 16), _mm256_set1_epi32(1));
-    const __m256i rounded = _mm256_srli_epi32(_mm256_add_epi32(b, _mm256_add_epi32(lsb, _mm256_set1_epi32(0x7FFF))), 16);
-    const __m256i quiet = _mm256_or_si256(_mm256_srli_epi32(b, 16), _mm256_set1_epi32(0x0040));
-    const __m256 isnan = _mm256_cmp_ps(x, x, _CMP_UNORD_Q);
-    const __m256i r = _mm256_blendv_epi8(rounded, quiet, _mm256_castps_si256(isnan));
-    const __m256i packed = _mm256_packus_epi32(r, r);                         // per 128-bit lane
-    const __m256i ordered = _mm256_permute4x64_epi64(packed, 0x08);           // lanes 0 and 2
-    _mm_storeu_si128((__m128i*)out, _mm256_castsi256_si128(ordered));
+    if (DT == ZI_FP16) return _mm256_cvtps_ph(x, _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC);
+    // bf16 keeps the upper half of the fp32 pattern.  The dropped half decides: above one half of the
+    // kept unit the upper half goes up by one, exactly one half goes to the even neighbour, below
+    // stays.  (Signed compares are fine: the dropped half is at most 0xFFFF.)  A NaN keeps its upper
+    // half with the quiet bit set, so it can neither become an infinity nor carry into the sign.
+    const __m256i bits = _mm256_castps_si256(x);
+    const __m256i upper = _mm256_srli_epi32(bits, 16);
+    const __m256i dropped = _mm256_and_si256(bits, _mm256_set1_epi32(0xFFFF));
+    const __m256i half = _mm256_set1_epi32(0x8000);
+    const __m256i above = _mm256_cmpgt_epi32(dropped, half);
+    const __m256i tie = _mm256_cmpeq_epi32(dropped, half);
+    const __m256i odd = _mm256_cmpeq_epi32(_mm256_and_si256(upper, _mm256_set1_epi32(1)), _mm256_set1_epi32(1));
+    const __m256i up = _mm256_or_si256(above, _mm256_and_si256(tie, odd));           // all ones where rounding up
+    const __m256i rounded = _mm256_sub_epi32(upper, up);                               // minus (-1) = plus one
+    const __m256i nan = _mm256_castps_si256(_mm256_cmp_ps(x, x, _CMP_UNORD_Q));
+    const __m256i quiet = _mm256_or_si256(upper, _mm256_set1_epi32(0x0040));
+    const __m256i r = _mm256_blendv_epi8(rounded, quiet, nan);
+    const __m256i packed = _mm256_packus_epi32(r, r);                                  // per 128-bit half
+    return _mm256_castsi256_si128(_mm256_permute4x64_epi64(packed, 0x08));            // halves 0 and 2
 }
 
-template <int DT, bool L2>
-void step_range(float* p, float* m, float* v, const uint16_t* g, uint16_t* lp, int64_t lo, int64_t hi,
-                const Consts& c)
+// Lane mask with the first k of eight lanes set (k in 0..8).
+inline __m256i first_lanes(int k)
 {
-    const __m256 beta1 = _mm256_set1_ps(c.beta1), beta2 = _mm256_set1_ps(c.beta2);
-    const __m256 omb1 = _mm256_set1_ps(c.omb1), omb2 = _mm256_set1_ps(c.omb2), eps = _mm256_set1_ps(c.eps);
-    const __m256 step = _mm256_set1_ps(c.step_size), isb = _mm256_set1_ps(c.inv_sqrt_bc2);
-    const __m256 decay = _mm256_set1_ps(c.decay), wd = _mm256_set1_ps(c.weight_decay);
-    const __m256 gscale = _mm256_set1_ps(c.gscale);
-    int64_t i = lo;
-    for (; i + 8 <= hi; i += 8) {
-        __m256 gi = _mm256_mul_ps(widen8<DT>(g + i), gscale);
-        const __m256 pi = _mm256_loadu_ps(p + i);
-        if (L2) gi = _mm256_fmadd_ps(wd, pi, gi);
-        const __m256 m1 = _mm256_fmadd_ps(beta1, _mm256_loadu_ps(m + i), _mm256_mul_ps(omb1, gi));
-        const __m256 v1 = _mm256_fmadd_ps(beta2, _mm256_loadu_ps(v + i), _mm256_mul_ps(omb2, _mm256_mul_ps(gi, gi)));
-        const __m256 d = _mm256_fmadd_ps(_mm256_sqrt_ps(v1), isb, eps);
-        const __m256 q = _mm256_div_ps(m1, d);
-        const __m256 pd = _mm256_fnmadd_ps(decay, pi, pi);
-        const __m256 p1 = _mm256_fnmadd_ps(step, q, pd);
-        _mm256_storeu_ps(m + i, m1);
-        _mm256_storeu_ps(v + i, v1);
-        _mm256_storeu_ps(p + i, p1);
-        if (lp) narrow8<DT>(p1, lp + i);
-    }
-    for (; i < hi; ++i) step_scalar(p, m, v, g, lp, i, DT, c);
+    alignas(32) static const int32_t ramp[8] = {0, 1, 2, 3, 4, 5, 6, 7};
+    return _mm256_cmpgt_epi32(_mm256_set1_epi32(k), _mm256_load_si256((const __m256i*)ramp));
 }
+
+// ------------------------------------------------------------------------------------ the update
+
+template <int DT, bool L2>
+struct Updater {
+    __m256 beta1, beta2, omb1, omb2, eps, step_size, inv_sqrt_bc2, decay, wd, gscale;
+
+    Updater(const zi::StepConsts& c, float gs)
+        : beta1(_mm256_set1_ps(c.beta1)), beta2(_mm256_set1_ps(c.beta2)), omb1(_mm256_set1_ps(c.omb1)),
+          omb2(_mm256_set1_ps(c.omb2)), eps(_mm256_set1_ps(c.eps)), step_size(_mm256_set1_ps(c.step_size)),
+          inv_sqrt_bc2(_mm256_set1_ps(c.inv_sqrt_bc2)), decay(_mm256_set1_ps(c.decay)),
+          wd(_mm256_set1_ps(c.weight_decay)), gscale(_mm256_set1_ps(gs))
+    {
+    }
+
+    // Eight elements: state in, state out (in place in the arguments), low-precision copy returned.
+    inline __m128i eight(__m256& p, __m256& m, __m256& v, __m128i g16) const
+    {
+        __m256 g = _mm256_mul_ps(widen8<DT>(g16), gscale);
+        if (L2) g = _mm256_fmadd_ps(wd, p, g);
+        m = _mm256_fmadd_ps(beta1, m, _mm256_mul_ps(omb1, g));
+        v = _mm256_fmadd_ps(beta2, v, _mm256_mul_ps(omb2, _mm256_mul_ps(g, g)));
+        const __m256 denom = _mm256_fmadd_ps(_mm256_sqrt_ps(v), inv_sqrt_bc2, eps);
+        const __m256 ratio = _mm256_div_ps(m, denom);
+        p = _mm256_fnmadd_ps(step_size, ratio, _mm256_fnmadd_ps(decay, p, p));
+        return narrow8<DT>(p);
+    }
+
+    // Elements [lo, hi) of one tensor.
+    void range(float* p, float* m, float* v, const uint16_t* g, uint16_t* lp, int64_t lo, int64_t hi) const
+    {
+        int64_t i = lo;
+        for (; i + 8 <= hi; i += 8) {
+            __m256 pi = _mm256_loadu_ps(p + i), mi = _mm256_loadu_ps(m + i), vi = _mm256_loadu_ps(v + i);
+            const __m128i out = eight(pi, mi, vi, _mm_loadu_si128((const __m128i*)(g + i)));
+            _mm256_storeu_ps(p + i, pi);
+            _mm256_storeu_ps(m + i, mi);
+            _mm256_storeu_ps(v + i, vi);
+            if (lp) _mm_storeu_si128((__m128i*)(lp + i), out);
+        }
+        const int k = (int)(hi - i);
+        if (k > 0) {
+            // The same routine over a padded group: lanes beyond k hold zeros and are never stored.
+            const __m256i mask = first_lanes(k);
+            __m256 pi = _mm256_maskload_ps(p + i, mask), mi = _mm256_maskload_ps(m + i, mask),
+                   vi = _mm256_maskload_ps(v + i, mask);
+            alignas(16) uint16_t g8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            std::memcpy(g8, g + i, (size_t)k * 2);
+            const __m128i out = eight(pi, mi, vi, _mm_load_si128((const __m128i*)g8));
+            _mm256_maskstore_ps(p + i, mask, pi);
+            _mm256_maskstore_ps(m + i, mask, mi);
+            _mm256_maskstore_ps(v + i, mask, vi);
+            if (lp) {
+                alignas(16) uint16_t o8[8];
+                _mm_store_si128((__m128i*)o8, out);
+                std::memcpy(lp + i, o8, (size_t)k * 2);
+            }
+        }
+    }
+};
+
+// Sum of squares (in double) and non-finite test of elements [lo, hi); a short end goes through the
+// same eight-lane code on a zero-padded copy (zeros add nothing and are finite).
+template <int DT>
+void sumsq_range(const uint16_t* g, int64_t lo, int64_t hi, double& sum_out, bool& bad_out)
+{
+    const __m128i expmask = _mm_set1_epi16((short)(DT == ZI_BF16 ? 0x7F80 : 0x7C00));
+    __m256d acc_lo = _mm256_setzero_pd(), acc_hi = _mm256_setzero_pd();
+    __m128i bad = _mm_setzero_si128();
+    auto eight = [&](__m128i h) {
+        bad = _mm_or_si128(bad, _mm_cmpeq_epi16(_mm_and_si128(h, expmask), expmask));
+        const __m256 f = widen8<DT>(h);
+        const __m256d a = _mm256_cvtps_pd(_mm256_castps256_ps128(f));
+        const __m256d b = _mm256_cvtps_pd(_mm256_extractf128_ps(f, 1));
+        acc_lo = _mm256_fmadd_pd(a, a, acc_lo);
+        acc_hi = _mm256_fmadd_pd(b, b, acc_hi);
+    };
+    int64_t i = lo;
+    for (; i + 8 <= hi; i += 8) eight(_mm_loadu_si128((const __m128i*)(g + i)));
+    if (i < hi) {
+        alignas(16) uint16_t g8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        std::memcpy(g8, g + i, (size_t)(hi - i) * 2);
+        eight(_mm_load_si128((const __m128i*)g8));
+    }
+    alignas(32) double lanes[4];
+    _mm256_store_pd(lanes, _mm256_add_pd(acc_lo, acc_hi));
+    sum_out = (lanes[0] + lanes[1]) + (lanes[2] + lanes[3]);
+    bad_out = !_mm_testz_si128(bad, bad);
+}
+
+// ------------------------------------------------------------------------------------ threading
 
 // Runs fn(block) for block = 0..n_blocks-1 on n_threads threads (the caller's included).
 template <class F>
@@ -154,17 +182,24 @@ void parallel_blocks(int64_t n_blocks, int n_threads, F fn)
 
 constexpr int64_t kBlockElems = 1 << 18;   // 1 MiB of each fp32 array per block
 
-bool cpu_ok()
+struct Block {
+    int32_t tensor;
+    int64_t lo, hi;
+};
+
+std::vector<Block> blocks_of(const zi_tensor* t, int32_t n_tensors)
 {
-    return __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma") && __builtin_cpu_supports("f16c");
+    std::vector<Block> blocks;
+    for (int32_t i = 0; i < n_tensors; ++i)
+        for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
+            blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
+    return blocks;
 }
 
-zi_status check_common(const zi_tensor* t, int32_t n_tensors, int dt, int32_t n_threads)
+zi_status check_cpu_and_threads(int32_t n_threads)
 {
-    if (!cpu_ok()) return fail(ZI_ERR_UNSUPPORTED, "the host step needs a CPU with AVX2, FMA and F16C");
-    if (dt != ZI_BF16 && dt != ZI_FP16) return fail(ZI_ERR_INVALID_ARG, "unknown low-precision dtype %d", dt);
-    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
-    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
+    if (!(__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma") && __builtin_cpu_supports("f16c")))
+        return fail(ZI_ERR_UNSUPPORTED, "the host step needs a CPU with AVX2, FMA and F16C");
     if (n_threads < 1 || n_threads > 256) return fail(ZI_ERR_INVALID_ARG, "n_threads must be in 1..256");
     return ZI_OK;
 }
@@ -175,52 +210,22 @@ extern "C" zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi
                                        zi_norm_result* h_out, int32_t n_threads)
 {
     try {
-        if (zi_status st = check_common(t, n_tensors, (int)dt, n_threads)) return st;
-        if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
-            return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+        if (zi_status st = check_cpu_and_threads(n_threads)) return st;
+        if (zi_status st = check_dtype((int)dt)) return st;
+        if (zi_status st = check_grad_list(t, n_tensors, loss_scale)) return st;
         if (!h_out) return fail(ZI_ERR_INVALID_ARG, "h_out is NULL");
-        for (int32_t i = 0; i < n_tensors; ++i) {
-            if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-            if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
-            if (reinterpret_cast<uintptr_t>(t[i].g) % 2) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
-        }
         // One partial per block, summed in block order afterwards: the result does not depend on the
         // number of threads.
-        struct Block { int32_t tensor; int64_t lo, hi; };
-        std::vector<Block> blocks;
-        for (int32_t i = 0; i < n_tensors; ++i)
-            for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
-                blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
+        const std::vector<Block> blocks = blocks_of(t, n_tensors);
         std::vector<double> part(blocks.size(), 0.0);
         std::vector<uint8_t> flag(blocks.size(), 0);
-        const uint16_t expmask = dt == ZI_BF16 ? 0x7F80u : 0x7C00u;
         parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
             const Block& B = blocks[(size_t)b];
             const uint16_t* g = (const uint16_t*)t[B.tensor].g;
-            __m256d acc0 = _mm256_setzero_pd(), acc1 = _mm256_setzero_pd();
-            __m128i bad = _mm_setzero_si128();
-            const __m128i em = _mm_set1_epi16((short)expmask);
-            int64_t i = B.lo;
-            for (; i + 8 <= B.hi; i += 8) {
-                const __m128i h = _mm_loadu_si128((const __m128i*)(g + i));
-                bad = _mm_or_si128(bad, _mm_cmpeq_epi16(_mm_and_si128(h, em), em));
-                const __m256 f = dt == ZI_BF16 ? widen8<ZI_BF16>(g + i) : widen8<ZI_FP16>(g + i);
-                const __m256d lo = _mm256_cvtps_pd(_mm256_castps256_ps128(f));
-                const __m256d hi = _mm256_cvtps_pd(_mm256_extractf128_ps(f, 1));
-                acc0 = _mm256_fmadd_pd(lo, lo, acc0);
-                acc1 = _mm256_fmadd_pd(hi, hi, acc1);
-            }
-            double lanes[4];
-            _mm256_storeu_pd(lanes, _mm256_add_pd(acc0, acc1));
-            double s = (lanes[0] + lanes[1]) + (lanes[2] + lanes[3]);
-            bool f = !_mm_testz_si128(bad, bad);
-            for (; i < B.hi; ++i) {
-                if ((g[i] & expmask) == expmask) f = true;
-                const double x = (double)widen_scalar(g[i], (int)dt);
-                s = std::fma(x, x, s);
-            }
-            part[(size_t)b] = s;
-            flag[(size_t)b] = f;
+            bool bad = false;
+            if (dt == ZI_BF16) sumsq_range<ZI_BF16>(g, B.lo, B.hi, part[(size_t)b], bad);
+            else               sumsq_range<ZI_FP16>(g, B.lo, B.hi, part[(size_t)b], bad);
+            flag[(size_t)b] = bad;
         });
         double sum = 0.0;
         uint32_t found = 0;
@@ -243,58 +248,21 @@ extern "C" zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, z
                                         int32_t n_threads)
 {
     try {
-        if (zi_status st = check_common(t, n_tensors, (int)dt, n_threads)) return st;
-        if (!cfg) return fail(ZI_ERR_INVALID_ARG, "cfg is NULL");
-        if (cfg->step < 1) return fail(ZI_ERR_INVALID_ARG, "step must be >= 1");
-        if (!(cfg->beta1 >= 0.0f && cfg->beta1 < 1.0f) || !(cfg->beta2 >= 0.0f && cfg->beta2 < 1.0f))
-            return fail(ZI_ERR_INVALID_ARG, "betas must be in [0,1)");
-        if (!(cfg->eps >= 0.0f) || std::isinf(cfg->eps)) return fail(ZI_ERR_INVALID_ARG, "eps must be finite and >= 0");
-        if (!std::isfinite(cfg->lr) || !std::isfinite(cfg->weight_decay))
-            return fail(ZI_ERR_INVALID_ARG, "lr and weight_decay must be finite");
-        if (!(cfg->loss_scale > 0.0f) || std::isinf(cfg->loss_scale))
-            return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
-        if (std::isnan(cfg->max_grad_norm)) return fail(ZI_ERR_INVALID_ARG, "max_grad_norm is NaN");
-        if (cfg->mode != ZI_MODE_ADAMW && cfg->mode != ZI_MODE_ADAM_L2) return fail(ZI_ERR_INVALID_ARG, "unknown mode");
-        for (int32_t i = 0; i < n_tensors; ++i) {
-            if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-            if (t[i].numel == 0) continue;
-            if (!t[i].p || !t[i].m || !t[i].v || !t[i].g)
-                return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v and g must not be NULL", i);
-            if (reinterpret_cast<uintptr_t>(t[i].p) % 4 || reinterpret_cast<uintptr_t>(t[i].m) % 4 ||
-                reinterpret_cast<uintptr_t>(t[i].v) % 4)
-                return fail(ZI_ERR_ALIGNMENT, "tensor %d: p, m, v must be 4-byte aligned", i);
-            if (reinterpret_cast<uintptr_t>(t[i].g) % 2 || reinterpret_cast<uintptr_t>(t[i].p_lp) % 2)
-                return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
-        }
+        if (zi_status st = check_cpu_and_threads(n_threads)) return st;
+        if (zi_status st = check_dtype((int)dt)) return st;
+        if (zi_status st = check_config(cfg)) return st;
+        if (zi_status st = check_step_tensors(t, n_tensors)) return st;
         if (h_norm && h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
 
-        // per-step scalars: double, each rounded once to fp32 (same expressions as the GPU path's host side)
-        Consts c{};
-        const double b1 = (double)cfg->beta1, b2 = (double)cfg->beta2;
-        const double bc1 = 1.0 - std::pow(b1, (double)cfg->step);
-        const double bc2 = 1.0 - std::pow(b2, (double)cfg->step);
-        c.beta1 = cfg->beta1;
-        c.beta2 = cfg->beta2;
-        c.omb1 = (float)(1.0 - b1);
-        c.omb2 = (float)(1.0 - b2);
-        c.eps = cfg->eps;
-        c.step_size = (float)((double)cfg->lr / bc1);
-        c.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
-        c.l2 = cfg->mode == ZI_MODE_ADAM_L2;
-        c.decay = c.l2 ? 0.0f : (float)((double)cfg->lr * (double)cfg->weight_decay);
-        c.weight_decay = cfg->weight_decay;
-        double clip = 1.0;
-        if (h_norm) {
-            const double mx = (double)cfg->max_grad_norm;
-            if (cfg->max_grad_norm > 0.0f && h_norm->norm + 1e-6 > mx) clip = mx / (h_norm->norm + 1e-6);
-        }
-        c.gscale = (float)(clip / (double)cfg->loss_scale);
+        const zi::StepConsts c = make_consts(*cfg);
+        const float gs = h_norm ? gradient_factor(h_norm->sumsq, c) : c.host_gscale;
+        const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
+        const Updater<ZI_BF16, false> bf(c, gs);
+        const Updater<ZI_BF16, true> bf_l2(c, gs);
+        const Updater<ZI_FP16, false> hf(c, gs);
+        const Updater<ZI_FP16, true> hf_l2(c, gs);
 
-        struct Block { int32_t tensor; int64_t lo, hi; };
-        std::vector<Block> blocks;
-        for (int32_t i = 0; i < n_tensors; ++i)
-            for (int64_t lo = 0; lo < t[i].numel; lo += kBlockElems)
-                blocks.push_back({i, lo, std::min(lo + kBlockElems, t[i].numel)});
+        const std::vector<Block> blocks = blocks_of(t, n_tensors);
         parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
             const Block& B = blocks[(size_t)b];
             const zi_tensor& T = t[B.tensor];
@@ -302,11 +270,11 @@ extern "C" zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, z
             const uint16_t* g = (const uint16_t*)T.g;
             uint16_t* lp = (uint16_t*)T.p_lp;
             if (dt == ZI_BF16) {
-                if (c.l2) step_range<ZI_BF16, true>(p, m, v, g, lp, B.lo, B.hi, c);
-                else      step_range<ZI_BF16, false>(p, m, v, g, lp, B.lo, B.hi, c);
+                if (l2) bf_l2.range(p, m, v, g, lp, B.lo, B.hi);
+                else    bf.range(p, m, v, g, lp, B.lo, B.hi);
             } else {
-                if (c.l2) step_range<ZI_FP16, true>(p, m, v, g, lp, B.lo, B.hi, c);
-                else      step_range<ZI_FP16, false>(p, m, v, g, lp, B.lo, B.hi, c);
+                if (l2) hf_l2.range(p, m, v, g, lp, B.lo, B.hi);
+                else    hf.range(p, m, v, g, lp, B.lo, B.hi);
             }
         });
         return ZI_OK;

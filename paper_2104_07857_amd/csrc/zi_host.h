@@ -10,13 +10,10 @@
 #include <vector>
 
 #include "zi_internal.h"
+#include "zi_checks.h"
 
 namespace zi {
 namespace host {
-
-// Stores the calling thread's error text (returned by zi_last_error) and passes the status through.
-zi_status fail(zi_status st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
-const char* last_error();
 
 #define ZI_HIP(call)                                                                                  \
     do {                                                                                              \
@@ -26,8 +23,6 @@ const char* last_error();
             return ::zi::host::fail(ZI_ERR_HIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
         }                                                                                             \
     } while (0)
-
-inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 // What kind of memory an address is: 0 device, 1 page-locked host, 2 ordinary host, -1 anything else,
 // -2 if the HIP runtime cannot answer (no usable device).
@@ -88,71 +83,6 @@ inline zi_status check_kernel_visible(const void* p, size_t bytes, int tensor, c
 {
     PointerChecker c;
     return c.check(p, bytes, tensor, name);
-}
-
-inline zi_status check_dtype(int dt)
-{
-    if (dt != ZI_BF16 && dt != ZI_FP16) return fail(ZI_ERR_INVALID_ARG, "unknown low-precision dtype %d", dt);
-    return ZI_OK;
-}
-
-inline zi_status check_config(const zi_adamw_config* c)
-{
-    if (!c) return fail(ZI_ERR_INVALID_ARG, "cfg is NULL");
-    if (c->step < 1) return fail(ZI_ERR_INVALID_ARG, "step must be >= 1 (got %lld)", (long long)c->step);
-    if (!(c->beta1 >= 0.0f && c->beta1 < 1.0f)) return fail(ZI_ERR_INVALID_ARG, "beta1 must be in [0,1)");
-    if (!(c->beta2 >= 0.0f && c->beta2 < 1.0f)) return fail(ZI_ERR_INVALID_ARG, "beta2 must be in [0,1)");
-    if (!(c->eps >= 0.0f) || std::isinf(c->eps)) return fail(ZI_ERR_INVALID_ARG, "eps must be finite and >= 0");
-    if (!std::isfinite(c->lr)) return fail(ZI_ERR_INVALID_ARG, "lr must be finite");
-    if (!std::isfinite(c->weight_decay)) return fail(ZI_ERR_INVALID_ARG, "weight_decay must be finite");
-    if (!(c->loss_scale > 0.0f) || std::isinf(c->loss_scale))
-        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
-    if (std::isnan(c->max_grad_norm)) return fail(ZI_ERR_INVALID_ARG, "max_grad_norm is NaN");
-    if (c->mode != ZI_MODE_ADAMW && c->mode != ZI_MODE_ADAM_L2)
-        return fail(ZI_ERR_INVALID_ARG, "unknown mode %d", c->mode);
-    return ZI_OK;
-}
-
-// Tensor list of a step: pointers present and aligned to their element size.
-inline zi_status check_step_tensors(const zi_tensor* t, int32_t n)
-{
-    if (n < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
-    if (n > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
-    for (int32_t i = 0; i < n; ++i) {
-        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-        if (t[i].numel == 0) continue;
-        if (!t[i].p || !t[i].m || !t[i].v || !t[i].g)
-            return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v and g must not be NULL", i);
-        if (!aligned(t[i].p, 4) || !aligned(t[i].m, 4) || !aligned(t[i].v, 4))
-            return fail(ZI_ERR_ALIGNMENT, "tensor %d: p, m, v must be 4-byte aligned", i);
-        if (!aligned(t[i].g, 2) || !aligned(t[i].p_lp, 2))
-            return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
-        if (t[i].p == t[i].m || t[i].p == t[i].v || t[i].m == t[i].v || t[i].g == t[i].p_lp)
-            return fail(ZI_ERR_INVALID_ARG, "tensor %d: arrays must not alias each other", i);
-    }
-    return ZI_OK;
-}
-
-// Per-step constants, in double, each rounded once to fp32.
-inline zi::StepConsts make_consts(const zi_adamw_config& c)
-{
-    zi::StepConsts k{};
-    const double b1 = (double)c.beta1, b2 = (double)c.beta2;
-    const double bc1 = 1.0 - std::pow(b1, (double)c.step);
-    const double bc2 = 1.0 - std::pow(b2, (double)c.step);
-    k.beta1 = c.beta1;
-    k.beta2 = c.beta2;
-    k.omb1 = (float)(1.0 - b1);
-    k.omb2 = (float)(1.0 - b2);
-    k.eps = c.eps;
-    k.step_size = (float)((double)c.lr / bc1);
-    k.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(bc2));
-    k.decay = c.mode == ZI_MODE_ADAMW ? (float)((double)c.lr * (double)c.weight_decay) : 0.0f;
-    k.weight_decay = c.weight_decay;
-    k.loss_scale = c.loss_scale;
-    k.max_grad_norm = c.max_grad_norm;
-    k.host_gscale = (float)(1.0 / (double)c.loss_scale);
-    return k;
 }
 
 // Number of leading elements (0..63) the step handles one by one before its vector body.  Any value
@@ -271,10 +201,7 @@ inline zi_status check_norm_args(const zi_tensor* t, int32_t n_tensors, int dt, 
                           void* d_workspace, size_t workspace_bytes)
 {
     if (zi_status st = check_dtype(dt)) return st;
-    if (n_tensors < 0) return fail(ZI_ERR_INVALID_ARG, "n_tensors < 0");
-    if (n_tensors > 0 && !t) return fail(ZI_ERR_INVALID_ARG, "tensor list is NULL");
-    if (!(loss_scale > 0.0f) || std::isinf(loss_scale))
-        return fail(ZI_ERR_INVALID_ARG, "loss_scale must be finite and > 0");
+    if (zi_status st = check_grad_list(t, n_tensors, loss_scale)) return st;
     if (!d_out) return fail(ZI_ERR_INVALID_ARG, "d_out is NULL");
     if (!aligned(d_out, 8)) return fail(ZI_ERR_ALIGNMENT, "d_out must be 8-byte aligned");
     if (!d_workspace) return fail(ZI_ERR_INVALID_ARG, "d_workspace is NULL");
@@ -282,12 +209,6 @@ inline zi_status check_norm_args(const zi_tensor* t, int32_t n_tensors, int dt, 
     if (workspace_bytes < (size_t)zi::kMaxPartials * sizeof(zi::NormPartial))
         return fail(ZI_ERR_INVALID_ARG, "workspace too small: %zu < %zu", workspace_bytes,
                     (size_t)zi::kMaxPartials * sizeof(zi::NormPartial));
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        if (t[i].numel < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: numel < 0", i);
-        if (t[i].numel > 0 && !t[i].g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
-        if (!aligned(t[i].g, 2)) return fail(ZI_ERR_ALIGNMENT, "tensor %d: g must be 2-byte aligned", i);
-    }
-
     return ZI_OK;
 }
 

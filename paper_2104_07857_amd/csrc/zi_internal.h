@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "zi.h"
+#include "zi_checks.h"
 
 namespace zi {
 
@@ -45,14 +46,6 @@ struct NormPartial {
     double sumsq;
     uint32_t found_inf;
     uint32_t pad;
-};
-
-// Per-step constants of the update, every one already rounded to fp32 on the host.
-struct StepConsts {
-    float beta1, beta2, omb1, omb2, eps, step_size, inv_sqrt_bc2, decay, weight_decay;
-    float loss_scale;      // as given by the caller
-    float max_grad_norm;   // <= 0: no clipping
-    float host_gscale;     // 1 / loss_scale, used when no norm result is given
 };
 
 // One tensor (or one segment of one) as the fused step sees it.  All pointers are device memory.

@@ -336,3 +336,33 @@ def test_every_gradient_pattern(dt):
     rep = compare_state(tuple(a[ok] for a in exp[:3]) + (exp[3][ok],), tuple(a[ok] for a in got[:3]) + (got[3][ok],),
                         dt, f"gradient patterns dt={dt} ")
     progress(f"all gradient patterns dt={dt}: {rep}")
+
+
+@pytest.mark.parametrize("dt", [zi.ZI_BF16, zi.ZI_FP16])
+def test_host_cpu_step_and_gpu_step_agree_bit_for_bit(dt):
+    """The explicit host-CPU entry points against the HIP kernels on the same values (both follow the one
+    written operation order): same norm to rounding, same p, m, v and copy, same skip decision."""
+    n = 300_007
+    spec = zi_synth.StateSpec(4242 + dt, dt, g_std=1e-3 if dt == zi.ZI_BF16 else 65.536)
+    hp, hm, hv, hg = gen_numpy(spec, n)
+    kw = dict(step=10, loss_scale=1.0 if dt == zi.ZI_BF16 else 65536.0, max_grad_norm=0.05)
+    cfg = zi.make_config(**kw)
+    p, m, v, g = to_dev(hp), to_dev(hm), to_dev(hv), to_dev(hg)
+    lp = torch.zeros(n, dtype=torch.int16, device="cuda:0")
+    nb = NormBuffers()
+    tl = [(p, m, v, g, lp, n)]
+    zi.zi_grad_norm(tl, dt, kw["loss_scale"], nb.out, nb.ws)
+    zi.zi_adamw_step(tl, dt, cfg, nb.out)
+    torch.cuda.synchronize()
+    sumsq, norm, flag = nb.read()
+    hlp = np.zeros(n, np.uint16)
+    htl = [(hp, hm, hv, hg, hlp, n)]
+    r = zi.zi_host_grad_norm(htl, dt, kw["loss_scale"], 4)
+    assert r.found_inf == flag == 0 and abs(r.sumsq - sumsq) <= 1e-12 * sumsq
+    # the step gets the very sum the GPU step read (the two reductions group their double sums differently)
+    shared = zi.zi_norm_result(sumsq, norm, flag, 0)
+    assert zi.zi_host_adamw_step(htl, dt, cfg, shared, 4) == zi.ZI_OK
+    for name, h, d in (("p", hp, p), ("m", hm, m), ("v", hv, v)):
+        assert np.array_equal(h.view(np.uint32), to_np(d).view(np.uint32)), name
+    assert np.array_equal(hlp, to_np(lp))
+    progress(f"host-CPU step == GPU step on {n} elements, dt={dt}")
