@@ -185,12 +185,16 @@ zi_status zi_norm_refresh(zi_norm_result* d_result, float loss_scale, void* hip_
  * Fused AdamW step over HBM-resident state (Sections 3 and 4.1; equations in
  * the header comment).  All arrays of every tensor are device memory; p, m, v
  * are updated in place and p_lp (if not NULL) receives the low-precision copy.
- * No two arrays may overlap.
+ * No two arrays may overlap: within a tensor the five byte ranges are checked
+ * pairwise (ZI_ERR_INVALID_ARG); arrays of different tensors must not overlap
+ * either (not checked).
  * d_norm: device result of zi_grad_norm on the same gradients, or NULL.  With
  * NULL there is no overflow check and no clipping: gscale = 1 / loss_scale.
  * With a result, the kernels read it on the device: found_inf != 0 skips the
- * whole step, otherwise the clip factor is derived from d_norm->norm.  The
- * loss_scale given to zi_grad_norm must equal cfg->loss_scale.
+ * whole step, otherwise the clip factor is derived from d_norm->sumsq and
+ * cfg->loss_scale (norm = sqrt(sumsq) / cfg->loss_scale; the result's own
+ * `norm` field is informational and is not read, so the scale that was given
+ * to zi_grad_norm does not matter here).
  * Asynchronous on hip_stream; the return value is ZI_OK even when the device
  * will skip the step (read d_norm->found_inf to learn of it).
  */
@@ -397,8 +401,10 @@ zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype 
                              const zi_norm_result* h_norm, int32_t n_threads);
 
 /*
- * HBM stream probe (a measurement aid): one launch with the fused step's access shape and no
- * arithmetic, over `bytes` (positive multiple of 16) of 16-byte aligned device memory.
+ * HBM stream probe (a measurement aid): one launch that streams `bytes` (positive multiple of 16)
+ * of 16-byte aligned device memory with no arithmetic, shaped the way that measured best for a plain
+ * stream on this device (single-wavefront workgroups, 4 KiB contiguous per wavefront, non-temporal
+ * accesses, six wavefronts per compute unit, XCD-aware tile order).
  * mode 0 = read d_a; mode 1 = copy d_a to d_b (non-overlapping); mode 2 = update d_a in place
  * (every fp32 value + 1).  Asynchronous on hip_stream.  Timing it gives the bandwidth a pure
  * read, a 1:1 copy and an in-place read-modify-write reach on this device, i.e. the practical

@@ -207,7 +207,7 @@ extern "C" zi_status zi_hbm_probe(void* d_a, void* d_b, size_t bytes, int32_t mo
     if (!d_a) return fail(ZI_ERR_INVALID_ARG, "d_a is NULL");
     if (mode == 1 && !d_b) return fail(ZI_ERR_INVALID_ARG, "d_b is NULL");
     if (bytes < 16 || bytes % 16) return fail(ZI_ERR_INVALID_ARG, "bytes must be a positive multiple of 16");
-    if (bytes / 16 / zi::kThreads > 0x7FFFFFFFull) return fail(ZI_ERR_INVALID_ARG, "bytes too large for one launch");
+    if (bytes / 16 / 256 >= 0x7FFFFFFFull) return fail(ZI_ERR_INVALID_ARG, "bytes too large for one launch");
     if (!aligned(d_a, 16) || !aligned(d_b, 16)) return fail(ZI_ERR_ALIGNMENT, "buffers must be 16-byte aligned");
     if (zi_status st = check_kernel_visible(d_a, bytes, -1, "d_a")) return st;
     if (mode == 1)

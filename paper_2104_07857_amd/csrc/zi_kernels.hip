@@ -82,14 +82,16 @@ __device__ __forceinline__ void adamw_element(float& p, float& m, float& v, floa
     v = v1;
 }
 
-// Skip decision and gradient factor, from the device-resident norm result.
+// Skip decision and gradient factor, from the device-resident norm result.  The norm is derived
+// here from the sum of squares and the step's own loss scale (not read from the result's `norm`
+// field), so the scale given to the reduction cannot disagree with the one the step unscales by.
 // Returns false if the step must be skipped.
 __device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, const StepConsts& c, float& gscale)
 {
     gscale = c.host_gscale;
     if (d_norm) {
         if (d_norm->found_inf) return false;
-        const double norm = d_norm->norm;
+        const double norm = __builtin_sqrt(d_norm->sumsq) / (double)c.loss_scale;
         const double mx = (double)c.max_grad_norm;
         double clip = 1.0;
         if (c.max_grad_norm > 0.0f && norm + 1e-6 > mx) clip = mx / (norm + 1e-6);
@@ -517,33 +519,65 @@ hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, flo
 
 // -------------------------------------------------------------- plain streams (measurement aid)
 
-// The same access shape as the fused step (one 16-byte vector per lane, non-temporal, one short
-// tile per workgroup) with no arithmetic: what the memory system gives a pure read, a 1:1 copy and
-// an in-place read-modify-write.  These are the ceilings the fused step is compared with.
+// What the memory system gives a pure read, a 1:1 copy and an in-place read-modify-write of one
+// array, launched the way that measured best for such streams on this device: single-wavefront
+// workgroups, four 16-byte vectors per lane (4 KiB contiguous per wavefront), non-temporal accesses,
+// residency capped at six wavefronts per compute unit by unused dynamic LDS, and the same XCD-aware
+// tile renumbering as the fused step.  These are the ceilings the fused step is compared with.
+constexpr int kProbeUnroll = 4;
+constexpr int kProbeTileVecs = 64 * kProbeUnroll;
+
 template <int MODE>
-__global__ __launch_bounds__(kThreads) void hbm_probe_kernel(f32x4* __restrict__ a, f32x4* __restrict__ b, int64_t n4,
-                                                            float* sink)
+__global__ __launch_bounds__(64) void hbm_probe_kernel(f32x4* __restrict__ a, f32x4* __restrict__ b, int64_t n4,
+                                                       float* sink)
 {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= n4) return;
-    f32x4 x = load_stream(a + i);
-    if constexpr (MODE == 0) {
-        if (x.x + x.y + x.z + x.w == 1.2345678e-30f) *sink = 1.0f;   // keeps the load alive
-    } else if constexpr (MODE == 1) {
-        store_stream(b + i, x);
+    const int64_t ntiles = (n4 + kProbeTileVecs - 1) / kProbeTileVecs;
+    constexpr uint32_t run = kXcds * (uint32_t)kStepXcdRun;
+    const uint32_t block = blockIdx.x;
+    const uint32_t r = block % run, base = block - r;
+    uint32_t nb = block;
+    if ((int64_t)base + run <= ntiles) nb = base + (r % kXcds) * (uint32_t)kStepXcdRun + r / kXcds;
+    const int64_t i0 = (int64_t)nb * kProbeTileVecs + threadIdx.x;
+    f32x4 x[kProbeUnroll];
+    if ((int64_t)(nb + 1) * kProbeTileVecs <= n4) {
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) x[u] = load_stream(a + i0 + u * 64);
+        if constexpr (MODE == 0) {
+            float s = 0.0f;
+#pragma unroll
+            for (int u = 0; u < kProbeUnroll; ++u) s += x[u].x + x[u].y + x[u].z + x[u].w;
+            if (s == 1.2345678e-30f) *sink = 1.0f;   // keeps the loads alive
+        } else if constexpr (MODE == 1) {
+#pragma unroll
+            for (int u = 0; u < kProbeUnroll; ++u) store_stream(b + i0 + u * 64, x[u]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kProbeUnroll; ++u) store_stream(a + i0 + u * 64, x[u] + 1.0f);
+        }
     } else {
-        x += 1.0f;
-        store_stream(a + i, x);
+        for (int u = 0; u < kProbeUnroll; ++u) {
+            const int64_t i = i0 + u * 64;
+            if (i >= n4) break;
+            const f32x4 y = load_stream(a + i);
+            if constexpr (MODE == 0) {
+                if (y.x + y.y + y.z + y.w == 1.2345678e-30f) *sink = 1.0f;
+            } else if constexpr (MODE == 1) {
+                store_stream(b + i, y);
+            } else {
+                store_stream(a + i, y + 1.0f);
+            }
+        }
     }
 }
 
 hipError_t launch_hbm_probe(void* a, void* b, int64_t n4, int mode, float* sink, hipStream_t s)
 {
     if (n4 <= 0) return hipSuccess;
-    const dim3 grid((uint32_t)((n4 + kThreads - 1) / kThreads)), block(kThreads);
-    if (mode == 0) hipLaunchKernelGGL(hbm_probe_kernel<0>, grid, block, 0, s, (f32x4*)a, (f32x4*)b, n4, sink);
-    else if (mode == 1) hipLaunchKernelGGL(hbm_probe_kernel<1>, grid, block, 0, s, (f32x4*)a, (f32x4*)b, n4, sink);
-    else hipLaunchKernelGGL(hbm_probe_kernel<2>, grid, block, 0, s, (f32x4*)a, (f32x4*)b, n4, sink);
+    const dim3 grid((uint32_t)((n4 + kProbeTileVecs - 1) / kProbeTileVecs)), block(64);
+    const unsigned lds = kStepOccupancyLds;
+    if (mode == 0) hipLaunchKernelGGL(hbm_probe_kernel<0>, grid, block, lds, s, (f32x4*)a, (f32x4*)b, n4, sink);
+    else if (mode == 1) hipLaunchKernelGGL(hbm_probe_kernel<1>, grid, block, lds, s, (f32x4*)a, (f32x4*)b, n4, sink);
+    else hipLaunchKernelGGL(hbm_probe_kernel<2>, grid, block, lds, s, (f32x4*)a, (f32x4*)b, n4, sink);
     return hipGetLastError();
 }
 

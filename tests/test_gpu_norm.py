@@ -105,8 +105,10 @@ def test_constant_closed_form():
     progress("norm closed form ok")
 
 
-def test_hbm_probe_modes_do_what_they_say():
-    n = (1 << 20) + 4
+@pytest.mark.parametrize("n", [4, 1020, (1 << 20) + 4, 3 * (1 << 20) + 8 * 1000 + 4])
+def test_hbm_probe_modes_do_what_they_say(n):
+    # sizes: less than one lane group, a ragged single tile, one complete XCD run of 8 x 128 tiles plus
+    # one vector, and several runs followed by an incomplete one
     a = torch.arange(n, dtype=torch.float32, device="cuda:0")
     b = torch.zeros(n + 4, dtype=torch.float32, device="cuda:0")
     ref = a.clone()
