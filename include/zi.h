@@ -207,7 +207,9 @@ zi_status zi_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, c
  * staged low-precision copy), three HIP streams (host-to-device,
  * compute, device-to-host; all at default priority) and the events that order
  * slot reuse (Section 6.3: a small pool of reused buffers serves the whole
- * state).  Created once; step calls allocate nothing.
+ * state).  Created once; step calls allocate no device or pinned memory and start no thread (the
+ * ring's CPU threads are created with the ring and parked between calls; the host-side plan of a
+ * call reuses buffers that grow only when a longer tensor list than ever before arrives).
  * chunk_bytes_per_array: positive multiple of 4096 (64 MiB is the usual value).
  * n_slots: 2..8.  device: HIP device ordinal.
  */
@@ -250,6 +252,43 @@ zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tens
                                 size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Gradient offload as the gradients are produced (Section 6.2: during the backward pass each
+ * gradient partition is moved to slow memory, overlapped with the computation that produces the
+ * next one).  zi_grad_offload enqueues the copy of `bytes` from device memory d_src to PINNED host
+ * memory h_dst on the engine's device-to-host stream, ordered after everything already enqueued on
+ * producer_stream (an event recorded there), and returns at once: the producer stream is not
+ * blocked and may go on with the next partition while this one drains.  d_src must stay untouched
+ * until the copy is done.
+ * Completion: zi_grad_offload_wait blocks the host until every offload issued so far has landed;
+ * zi_grad_offload_order makes consumer_stream wait for them instead (no host blocking).
+ * zi_grad_norm_streamed, zi_adamw_step_streamed and zi_adamw_step_cpu on the same engine order
+ * themselves after outstanding offloads, so the host copies can be handed to them directly.
+ * Calls on one engine must not overlap in time (an engine serves one call at a time).
+ */
+zi_status zi_grad_offload(zi_engine* e, const void* d_src, void* h_dst, size_t bytes, void* producer_stream);
+zi_status zi_grad_offload_wait(zi_engine* e);
+zi_status zi_grad_offload_order(zi_engine* e, void* consumer_stream);
+
+/*
+ * The step on the host CPUs with the link carrying only the 2-byte arrays (Section 5.2.2: with the
+ * optimizer states in CPU memory the step runs on the CPUs; gradients come down, updated
+ * low-precision parameters go up: 2 + 2 bytes per element over the link instead of 12 + 12).
+ * p, m, v: host memory of any kind, updated in place by n_threads CPU threads (AVX2 / FMA / F16C,
+ * the arithmetic of zi_host_adamw_step).  g, p_lp: DEVICE memory — each chunk of gradients is
+ * fetched into the engine's pinned ring, stepped, and the chunk of the copy is shipped back, the
+ * fetch of later chunks and the upload of earlier ones overlapping the CPUs' work — or host memory,
+ * used in place.  Device-resident g / p_lp need ZI_OPT_HOST_RING_SLOTS >= 3.
+ * d_norm: device result of zi_grad_norm or NULL; read back first; found_inf != 0 returns
+ * ZI_SKIPPED_OVERFLOW with nothing touched.  The engine's streams first wait for hip_stream.
+ * BLOCKING: on return the host state and p_lp are complete.  Results are bit-identical to
+ * zi_adamw_step and zi_adamw_step_streamed on the same values.  This call is chosen explicitly;
+ * no GPU entry point falls back to it.  ZI_ERR_UNSUPPORTED on a CPU without those instructions.
+ */
+zi_status zi_adamw_step_cpu(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
+                            const zi_adamw_config* cfg, const zi_norm_result* d_norm, int32_t n_threads,
+                            void* hip_stream);
+
+/*
  * The same step with p, m, v in FILES (Section 5.2.2: with NVMe offload the state is brought to
  * faster memory and back in chunks, one chunk at a time; Section 6.3: bulk reads and writes issued
  * in parallel, into and out of reused pinned buffers, no further copies).  Each chunk is read by
@@ -283,15 +322,6 @@ typedef struct {
 zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                               const zi_adamw_config* cfg, const zi_norm_result* d_norm, void* hip_stream);
 
-/*
- * Storage probe: with the engine's thread pools and pinned ring, read `bytes` from fd_read
- * (from offset 0) and, at the same time, write `bytes` to fd_write (from offset 0); either
- * descriptor may be -1 to measure one direction alone.  bytes: positive multiple of 4096.
- * Reports the elapsed seconds: the file-tier bandwidth the streamed step is bounded by.
- */
-zi_status zi_engine_file_probe(zi_engine* e, int32_t fd_read, int32_t fd_write, size_t bytes,
-                               double* seconds_out);
-
 /* Figures of the engine's last streamed step (host memory, filled by the call). */
 typedef struct {
     double seconds;            /* first host-to-device issue .. last device-to-host completion */
@@ -308,7 +338,8 @@ zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
 /*
  * Engine options.
  * ZI_OPT_SKIP_KERNEL = 1 runs the identical copy pipeline without launching the
- * update (a measurement aid: the time of the pipeline with the update removed).
+ * update (a measurement aid like the calls of zi_probe.h: the time of the pipeline with the update
+ * removed).
  * ZI_OPT_MAX_INFLIGHT = k: before issuing a slot use the host waits for the use k positions back
  * to finish.  The default 2 keeps copy-in and copy-out in lockstep, which measured fastest and
  * steadiest; with n_slots = 3 the third slot then only decouples the host's issue from completion.
@@ -328,18 +359,6 @@ typedef enum {
     ZI_OPT_MAX_INFLIGHT = 3        /* 1..n_slots slot uses the host keeps in flight (default 2) */
 } zi_engine_option;
 zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t value);
-
-/*
- * Host-link probe: copies `bytes` between a pinned host buffer and the engine's
- * staging memory `repeats` times in pieces of the engine's chunk size and
- * reports the elapsed seconds.  mode 0 = host-to-device only, 1 = device-to-host
- * only, 2 = both directions at once on the engine's two copy streams (then
- * `bytes` move in EACH direction, from host_src and into host_dst).  Buffers
- * must be pinned and hold `bytes` each; host_dst may be NULL for mode 0 and
- * host_src for mode 1.  Blocking.
- */
-zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, void* host_dst, size_t bytes,
-                               int32_t mode, int32_t repeats, double* seconds_out);
 
 /*
  * Chunk plan of the streamed step, as a pure host function (no GPU needed):
@@ -399,18 +418,6 @@ zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype d
                             zi_norm_result* h_out, int32_t n_threads);
 zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, const zi_adamw_config* cfg,
                              const zi_norm_result* h_norm, int32_t n_threads);
-
-/*
- * HBM stream probe (a measurement aid): one launch that streams `bytes` (positive multiple of 16)
- * of 16-byte aligned device memory with no arithmetic, shaped the way that measured best for a plain
- * stream on this device (single-wavefront workgroups, 4 KiB contiguous per wavefront, non-temporal
- * accesses, six wavefronts per compute unit, XCD-aware tile order).
- * mode 0 = read d_a; mode 1 = copy d_a to d_b (non-overlapping); mode 2 = update d_a in place
- * (every fp32 value + 1).  Asynchronous on hip_stream.  Timing it gives the bandwidth a pure
- * read, a 1:1 copy and an in-place read-modify-write reach on this device, i.e. the practical
- * ceilings of the norm pass and of the fused step.
- */
-zi_status zi_hbm_probe(void* d_a, void* d_b, size_t bytes, int32_t mode, void* hip_stream);
 
 /* Pinned (page-locked, device-visible) host memory.  zi_pinned_free(NULL) is accepted. */
 zi_status zi_pinned_alloc(void** out, size_t bytes);

@@ -35,7 +35,7 @@ EXPORTS = [
     "zi_last_error", "zi_norm_workspace_bytes", "zi_grad_norm", "zi_adamw_step", "zi_engine_create",
     "zi_engine_destroy", "zi_adamw_step_streamed", "zi_engine_last_stats", "zi_engine_set_option",
     "zi_grad_norm_streamed", "zi_adamw_step_files", "zi_engine_file_probe", "zi_engine_link_probe", "zi_plan_chunks", "zi_pinned_alloc", "zi_pinned_free", "zi_hbm_probe",
-    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh", "zi_plan_step", "zi_grad_norm_noalloc",
+    "zi_host_grad_norm", "zi_host_adamw_step", "zi_norm_refresh", "zi_plan_step", "zi_grad_norm_noalloc", "zi_grad_offload", "zi_grad_offload_wait", "zi_grad_offload_order", "zi_adamw_step_cpu",
 ]
 
 
@@ -129,7 +129,16 @@ def lib() -> ctypes.CDLL:
         L.zi_engine_set_option.restype = ctypes.c_int
         L.zi_engine_set_option.argtypes = [vp, i32, i64]
         L.zi_engine_link_probe.restype = ctypes.c_int
-        L.zi_engine_link_probe.argtypes = [vp, vp, vp, sz, i32, i32, ctypes.POINTER(ctypes.c_double)]
+        L.zi_engine_link_probe.argtypes = [vp, vp, vp, sz, i32, sz, i32, ctypes.POINTER(ctypes.c_double)]
+        L.zi_grad_offload.restype = ctypes.c_int
+        L.zi_grad_offload.argtypes = [vp, vp, vp, sz, vp]
+        L.zi_grad_offload_wait.restype = ctypes.c_int
+        L.zi_grad_offload_wait.argtypes = [vp]
+        L.zi_grad_offload_order.restype = ctypes.c_int
+        L.zi_grad_offload_order.argtypes = [vp, vp]
+        L.zi_adamw_step_cpu.restype = ctypes.c_int
+        L.zi_adamw_step_cpu.argtypes = [vp, ctypes.POINTER(zi_tensor), i32, ctypes.c_int,
+                                        ctypes.POINTER(zi_adamw_config), vp, i32, vp]
         L.zi_plan_chunks.restype = ctypes.c_int
         L.zi_plan_chunks.argtypes = [ctypes.POINTER(i64), i32, i64, ctypes.POINTER(zi_chunk_segment), i64,
                                      ctypes.POINTER(i64), ctypes.POINTER(i64)]
@@ -299,11 +308,31 @@ def zi_engine_set_option(engine, option: int, value: int) -> int:
     return _check(lib().zi_engine_set_option(engine, int(option), int(value)))
 
 
-def zi_engine_link_probe(engine, host_src, host_dst, nbytes: int, mode: int, repeats: int = 1) -> float:
+def zi_engine_link_probe(engine, host_src, host_dst, nbytes: int, mode: int, piece_bytes: int = 0,
+                         depth: int = 2) -> float:
     sec = ctypes.c_double()
     _check(lib().zi_engine_link_probe(engine, _addr(host_src), _addr(host_dst), int(nbytes), int(mode),
-                                      int(repeats), ctypes.byref(sec)))
+                                      int(piece_bytes), int(depth), ctypes.byref(sec)))
     return sec.value
+
+
+def zi_grad_offload(engine, d_src, h_dst, nbytes: int, producer_stream=None) -> int:
+    return _check(lib().zi_grad_offload(engine, _addr(d_src), _addr(h_dst), int(nbytes), _stream(producer_stream)))
+
+
+def zi_grad_offload_wait(engine) -> int:
+    return _check(lib().zi_grad_offload_wait(engine))
+
+
+def zi_grad_offload_order(engine, consumer_stream=None) -> int:
+    return _check(lib().zi_grad_offload_order(engine, _stream(consumer_stream)))
+
+
+def zi_adamw_step_cpu(engine, tensors, dt: int, cfg: zi_adamw_config, d_norm=None, n_threads: int = 1,
+                      stream=None) -> int:
+    arr, n = _as_tensor_array(tensors)
+    return _check(lib().zi_adamw_step_cpu(engine, arr, n, int(dt), ctypes.byref(cfg) if cfg is not None else None,
+                                          _addr(d_norm), int(n_threads), _stream(stream)))
 
 
 def zi_plan_chunks(numel: Sequence[int], chunk_elems: int):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libzi.so")
-SOURCES = ["zi_kernels.hip", "zi_api.hip", "zi_plan.hip", "zi_engine.hip"]
+SOURCES = ["zi_kernels.hip", "zi_api.hip", "zi_plan.hip", "zi_engine.hip", "zi_offload.hip", "zi_probe.hip"]
 
 # -ffp-contract=off: the only fused multiply-adds are the ones the kernels write as fma.
 # Packed fp32 instructions are switched off for the device code.
@@ -33,7 +33,8 @@ def needs_build() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "zi.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + \
+           [os.path.join(ROOT, "include", f) for f in ("zi.h", "zi_probe.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -50,7 +51,7 @@ def build(force: bool = True, extra_flags=(), out: str | None = None) -> str:
     objs = []
     for src in HOST_SOURCES:
         obj = os.path.join(HERE, "_" + os.path.splitext(src)[0] + ".o")
-        subprocess.run(["g++", *HOST_FLAGS, "-I", os.path.join(ROOT, "include"), "-c", os.path.join(CSRC, src),
+        subprocess.run(["g++", *HOST_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", os.path.join(CSRC, src),
                         "-o", obj], check=True)
         objs.append(obj)
     cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC,

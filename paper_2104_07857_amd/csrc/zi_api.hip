@@ -199,24 +199,6 @@ extern "C" zi_status zi_plan_step(const zi_tensor* t, int32_t n_tensors, zi_step
     return ZI_OK;
 }
 
-// ================================================================================== HBM probe
-
-extern "C" zi_status zi_hbm_probe(void* d_a, void* d_b, size_t bytes, int32_t mode, void* hip_stream)
-{
-    if (mode < 0 || mode > 2) return fail(ZI_ERR_INVALID_ARG, "mode must be 0 (read), 1 (copy) or 2 (in-place update)");
-    if (!d_a) return fail(ZI_ERR_INVALID_ARG, "d_a is NULL");
-    if (mode == 1 && !d_b) return fail(ZI_ERR_INVALID_ARG, "d_b is NULL");
-    if (bytes < 16 || bytes % 16) return fail(ZI_ERR_INVALID_ARG, "bytes must be a positive multiple of 16");
-    if (bytes / 16 / 256 >= 0x7FFFFFFFull) return fail(ZI_ERR_INVALID_ARG, "bytes too large for one launch");
-    if (!aligned(d_a, 16) || !aligned(d_b, 16)) return fail(ZI_ERR_ALIGNMENT, "buffers must be 16-byte aligned");
-    if (zi_status st = check_kernel_visible(d_a, bytes, -1, "d_a")) return st;
-    if (mode == 1)
-        if (zi_status st = check_kernel_visible(d_b, bytes, -1, "d_b")) return st;
-    // mode 0 needs a place for a store that never happens: the first float of d_a itself
-    ZI_HIP(zi::launch_hbm_probe(d_a, d_b, (int64_t)(bytes / 16), mode, (float*)d_a, (hipStream_t)hip_stream));
-    return ZI_OK;
-}
-
 // ================================================================================ pinned memory
 
 extern "C" zi_status zi_pinned_alloc(void** out, size_t bytes)

@@ -126,5 +126,12 @@ inline zi_status check_grad_list(const zi_tensor* t, int32_t n_tensors, float lo
     return ZI_OK;
 }
 
+// The host-CPU step over elements [lo, hi) of one tensor (zi_cpu_step.cpp; AVX2 / FMA / F16C): the
+// routine behind zi_host_adamw_step, also used by the engine when the step runs on the CPUs while
+// gradients and the copy cross the link.  g / lp are indexed like p, m, v.  lp may be null.
+void host_step_range(const zi::StepConsts& c, float gscale, int dt, bool l2, float* p, float* m, float* v,
+                     const uint16_t* g, uint16_t* lp, int64_t lo, int64_t hi);
+bool host_step_supported();     // the CPU has the vector instructions the routine is written with
+
 }  // namespace host
 }  // namespace zi

@@ -198,13 +198,36 @@ std::vector<Block> blocks_of(const zi_tensor* t, int32_t n_tensors)
 
 zi_status check_cpu_and_threads(int32_t n_threads)
 {
-    if (!(__builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma") && __builtin_cpu_supports("f16c")))
+    if (!host_step_supported())
         return fail(ZI_ERR_UNSUPPORTED, "the host step needs a CPU with AVX2, FMA and F16C");
     if (n_threads < 1 || n_threads > 256) return fail(ZI_ERR_INVALID_ARG, "n_threads must be in 1..256");
     return ZI_OK;
 }
 
 }  // namespace
+
+namespace zi {
+namespace host {
+
+bool host_step_supported()
+{
+    return __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma") && __builtin_cpu_supports("f16c");
+}
+
+void host_step_range(const zi::StepConsts& c, float gscale, int dt, bool l2, float* p, float* m, float* v,
+                     const uint16_t* g, uint16_t* lp, int64_t lo, int64_t hi)
+{
+    if (dt == ZI_BF16) {
+        if (l2) Updater<ZI_BF16, true>(c, gscale).range(p, m, v, g, lp, lo, hi);
+        else    Updater<ZI_BF16, false>(c, gscale).range(p, m, v, g, lp, lo, hi);
+    } else {
+        if (l2) Updater<ZI_FP16, true>(c, gscale).range(p, m, v, g, lp, lo, hi);
+        else    Updater<ZI_FP16, false>(c, gscale).range(p, m, v, g, lp, lo, hi);
+    }
+}
+
+}  // namespace host
+}  // namespace zi
 
 extern "C" zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt, float loss_scale,
                                        zi_norm_result* h_out, int32_t n_threads)
@@ -257,25 +280,12 @@ extern "C" zi_status zi_host_adamw_step(const zi_tensor* t, int32_t n_tensors, z
         const zi::StepConsts c = make_consts(*cfg);
         const float gs = h_norm ? gradient_factor(h_norm->sumsq, c) : c.host_gscale;
         const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
-        const Updater<ZI_BF16, false> bf(c, gs);
-        const Updater<ZI_BF16, true> bf_l2(c, gs);
-        const Updater<ZI_FP16, false> hf(c, gs);
-        const Updater<ZI_FP16, true> hf_l2(c, gs);
-
         const std::vector<Block> blocks = blocks_of(t, n_tensors);
         parallel_blocks((int64_t)blocks.size(), n_threads, [&](int64_t b) {
             const Block& B = blocks[(size_t)b];
             const zi_tensor& T = t[B.tensor];
-            float *p = (float*)T.p, *m = (float*)T.m, *v = (float*)T.v;
-            const uint16_t* g = (const uint16_t*)T.g;
-            uint16_t* lp = (uint16_t*)T.p_lp;
-            if (dt == ZI_BF16) {
-                if (l2) bf_l2.range(p, m, v, g, lp, B.lo, B.hi);
-                else    bf.range(p, m, v, g, lp, B.lo, B.hi);
-            } else {
-                if (l2) hf_l2.range(p, m, v, g, lp, B.lo, B.hi);
-                else    hf.range(p, m, v, g, lp, B.lo, B.hi);
-            }
+            host_step_range(c, gs, (int)dt, l2, (float*)T.p, (float*)T.m, (float*)T.v, (const uint16_t*)T.g,
+                            (uint16_t*)T.p_lp, B.lo, B.hi);
         });
         return ZI_OK;
     } catch (const std::exception& ex) {

@@ -8,85 +8,26 @@
 #include <cstring>
 #include <new>
 
-#include "zi_host.h"
-#include "zi_io_pool.h"
+#include "zi_engine_internal.h"
 
 using namespace zi::host;
 
 namespace {
 
-constexpr int kMaxHostSlots = 16;
-// A slot holds p, m, v and a fourth array whose first half stages host-resident gradients and whose
-// second half stages a host-resident low-precision copy.
-constexpr int kSlotArrays = 4;
-
-}  // namespace
-
-struct zi_engine {
-    int device = 0;
-    size_t chunk_bytes = 0;            // per state array
-    int64_t chunk_elems = 0;
-    size_t array_bytes = 0;            // chunk_bytes + room for lead-in elements and a rounded-up last block
-    uint32_t magic = 0;
-
-    // HBM staging: n_slots slots of kSlotArrays arrays, three streams, events that order slot reuse.
-    int n_slots = 0;
-    char* staging = nullptr;
-    hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
-    hipEvent_t ev_h2d[8] = {}, ev_k[8] = {}, ev_d2h[8] = {};
-    hipEvent_t ev_in = nullptr, ev_out = nullptr;
-    zi_norm_result* h_norm = nullptr;  // pinned landing place of the norm result
-
-    // Pinned ring for state that is not page-locked (ordinary memory, files): n_hslots slots shaped
-    // like the HBM slots, filled and emptied by two small thread pools.
-    int n_hslots = 0;
-    char* hring = nullptr;
-    hipEvent_t ev_back[kMaxHostSlots] = {};
-    int copy_threads = 6;
-    CopyPool* pool_in = nullptr;
-    CopyPool* pool_out = nullptr;
-
-    // options and figures
-    int64_t skip_kernel = 0;
-    int max_inflight = 2;              // slot uses the host keeps in flight (<= n_slots)
-    zi_stream_stats stats{};
-
-    float* slot_array(int slot, int which) const
-    {
-        return reinterpret_cast<float*>(staging + ((size_t)slot * kSlotArrays + which) * array_bytes);
-    }
-    uint16_t* slot_g(int slot) const { return reinterpret_cast<uint16_t*>(slot_array(slot, 3)); }
-    uint16_t* slot_lp(int slot) const
-    {
-        return reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(slot_array(slot, 3)) + array_bytes / 2);
-    }
-    float* hslot_array(int hslot, int which) const
-    {
-        return reinterpret_cast<float*>(hring + ((size_t)hslot * kSlotArrays + which) * array_bytes);
-    }
-    uint16_t* hslot_g(int h) const { return reinterpret_cast<uint16_t*>(hslot_array(h, 3)); }
-    uint16_t* hslot_lp(int h) const
-    {
-        return reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(hslot_array(h, 3)) + array_bytes / 2);
-    }
-};
-
-namespace {
-
-constexpr uint32_t kEngineMagic = 0x5A49454Eu;
-
-zi_status check_engine(const zi_engine* e)
-{
-    if (!e) return fail(ZI_ERR_INVALID_ARG, "engine is NULL");
-    if (e->magic != kEngineMagic) return fail(ZI_ERR_INVALID_ARG, "engine is not valid (destroyed?)");
-    return ZI_OK;
-}
-
-// A pool of `n` copy threads, or null if memory or threads cannot be had.
-CopyPool* make_pool(int n)
+// A pool of `n` parked threads / one parked stage thread, or null if memory or threads cannot be had.
+TaskPool* make_pool(int n)
 {
     try {
-        return new CopyPool(n);
+        return new TaskPool(n);
+    } catch (const std::exception&) {
+        return nullptr;
+    }
+}
+
+StageThread* make_stage()
+{
+    try {
+        return new StageThread();
     } catch (const std::exception&) {
         return nullptr;
     }
@@ -94,12 +35,16 @@ CopyPool* make_pool(int n)
 
 void ring_release(zi_engine* e)
 {
+    delete e->stage_in;
+    delete e->stage_out;
+    e->stage_in = e->stage_out = nullptr;
     delete e->pool_in;
     delete e->pool_out;
     e->pool_in = e->pool_out = nullptr;
     for (int i = 0; i < kMaxHostSlots; ++i) {
         if (e->ev_back[i]) (void)hipEventDestroy(e->ev_back[i]);
-        e->ev_back[i] = nullptr;
+        if (e->ev_fill[i]) (void)hipEventDestroy(e->ev_fill[i]);
+        e->ev_back[i] = e->ev_fill[i] = nullptr;
     }
     if (e->hring) (void)hipHostFree(e->hring);
     e->hring = nullptr;
@@ -113,6 +58,9 @@ void engine_release(zi_engine* e)
         if (e->ev_k[i]) (void)hipEventDestroy(e->ev_k[i]);
         if (e->ev_d2h[i]) (void)hipEventDestroy(e->ev_d2h[i]);
     }
+    for (int i = 0; i < kOffloadEvents; ++i)
+        if (e->ev_offload[i]) (void)hipEventDestroy(e->ev_offload[i]);
+    if (e->ev_offload_done) (void)hipEventDestroy(e->ev_offload_done);
     if (e->ev_in) (void)hipEventDestroy(e->ev_in);
     if (e->ev_out) (void)hipEventDestroy(e->ev_out);
     if (e->s_h2d) (void)hipStreamDestroy(e->s_h2d);
@@ -121,6 +69,8 @@ void engine_release(zi_engine* e)
     if (e->staging) (void)hipFree(e->staging);
     if (e->h_norm) (void)hipHostFree(e->h_norm);
     ring_release(e);
+    delete e->pool_step;
+    e->pool_step = nullptr;
     e->magic = 0;
     delete e;
 }
@@ -168,13 +118,15 @@ extern "C" zi_status zi_engine_create(zi_engine** out, int32_t device, size_t ch
     ZI_HIP_E(hipStreamCreateWithFlags(&e->s_h2d, hipStreamNonBlocking));
     ZI_HIP_E(hipStreamCreateWithFlags(&e->s_k, hipStreamNonBlocking));
     ZI_HIP_E(hipStreamCreateWithFlags(&e->s_d2h, hipStreamNonBlocking));
-    for (int i = 0; i < n_slots; ++i) {
+    for (int i = 0; i < 8; ++i) {      // all eight: the link probe paces up to eight pieces per direction
         ZI_HIP_E(hipEventCreateWithFlags(&e->ev_h2d[i], hipEventDisableTiming));
         ZI_HIP_E(hipEventCreateWithFlags(&e->ev_k[i], hipEventDisableTiming));
         ZI_HIP_E(hipEventCreateWithFlags(&e->ev_d2h[i], hipEventDisableTiming));
     }
     ZI_HIP_E(hipEventCreateWithFlags(&e->ev_in, hipEventDisableTiming));
     ZI_HIP_E(hipEventCreateWithFlags(&e->ev_out, hipEventDisableTiming));
+    for (int i = 0; i < kOffloadEvents; ++i) ZI_HIP_E(hipEventCreateWithFlags(&e->ev_offload[i], hipEventDisableTiming));
+    ZI_HIP_E(hipEventCreateWithFlags(&e->ev_offload_done, hipEventDisableTiming));
 #undef ZI_HIP_E
     e->magic = kEngineMagic;
     *out = e;
@@ -244,6 +196,7 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
         }
         for (int i = 0; i < (int)value; ++i) {
             he = hipEventCreateWithFlags(&e->ev_back[i], hipEventDisableTiming);
+            if (he == hipSuccess) he = hipEventCreateWithFlags(&e->ev_fill[i], hipEventDisableTiming);
             if (he != hipSuccess) {
                 (void)hipGetLastError();
                 ring_release(e);
@@ -252,7 +205,9 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
         }
         e->pool_in = make_pool(e->copy_threads);
         e->pool_out = make_pool(e->copy_threads);
-        if (!e->pool_in || !e->pool_out) {
+        e->stage_in = make_stage();
+        e->stage_out = make_stage();
+        if (!e->pool_in || !e->pool_out || !e->stage_in || !e->stage_out) {
             ring_release(e);
             return fail(ZI_ERR_NOMEM, "could not start the copy threads");
         }
@@ -264,71 +219,49 @@ extern "C" zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t 
 
 namespace {
 
-enum { kSrcPinned = 0, kSrcPageable = 1, kSrcFile = 2 };
-
-// Where the fp32 state of one tensor lives for the streamed step.
-struct StateSrc {
-    int kind;
-    char* ptr[3];        // p, m, v (memory kinds)
-    int fd[3];           // file kind
-    int64_t off[3];
-    bool direct[3];      // descriptor was opened with O_DIRECT
-    const void* g;       // device, or host when g_host
-    void* p_lp;          // device, or host when lp_host; may be null
-    bool g_host;         // gradients live in host memory and are staged chunk by chunk
-    bool lp_host;        // the low-precision copy is written back to host memory
-    int64_t numel;
-};
-
-// After a failed call: wait for whatever the engine's streams still hold, keeping the first error.
-void drain_streams(zi_engine* e)
+// Every array a kernel or a copy engine will touch is looked at before anything is issued: a
+// device-resident array over its whole byte range, a host array at its first and last byte.
+// Returns the memory kind of the array (0 device, 1 page-locked host, 2 ordinary host).
+zi_status classify_array(PointerChecker& reach, const void* p, size_t bytes, int tensor, const char* name, int& kind)
 {
-    (void)hipStreamSynchronize(e->s_h2d);
-    (void)hipStreamSynchronize(e->s_k);
-    (void)hipStreamSynchronize(e->s_d2h);
-    (void)hipGetLastError();
+    kind = memory_kind(p);
+    if (kind == -2) return fail(ZI_ERR_HIP, "no usable HIP device (pointer query failed)");
+    if (kind < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: %s is neither device nor host memory", tensor, name);
+    if (kind == 0) return reach.check(p, bytes, tensor, name);
+    const int last = memory_kind(static_cast<const char*>(p) + bytes - 1);
+    if (last != kind)
+        return fail(ZI_ERR_INVALID_ARG, "tensor %d: %s (%zu bytes) does not lie in one kind of host memory", tensor,
+                    name, bytes);
+    return ZI_OK;
 }
 
 // The chunk pipeline.  `staged` = the state is not page-locked memory and travels through the
 // engine's pinned ring (CPU threads fill and empty the ring slots).
-zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool staged, zi_lp_dtype dt,
-                       const zi_adamw_config* cfg, const zi_norm_result* d_norm, hipStream_t user)
-{
-    const int32_t n_tensors = (int32_t)src.size();
-    std::vector<int64_t> numel((size_t)n_tensors);
-    for (int32_t i = 0; i < n_tensors; ++i) numel[(size_t)i] = src[(size_t)i].numel;
-    std::vector<Segment> segs;
-    int64_t n_uses = 0;
-    try {
-        plan_chunks(numel.data(), n_tensors, e->chunk_elems, segs, n_uses);
-    } catch (const std::bad_alloc&) {
-        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
+struct StreamedRun {
+    zi_engine* e;
+    const std::vector<StateSrc>& src;
+    const std::vector<Segment>& segs;
+    const std::vector<size_t>& use_begin;
+    int64_t n_uses;
+    int n_h;
+
+    // Progress shared by the three actors of the ring path (gather thread, the caller's thread,
+    // scatter thread), under one mutex.
+    std::mutex mu;
+    std::condition_variable cv;
+    int64_t gathered = 0, issued = 0, scattered = 0;
+    bool abort = false;
+    bool io_error = false;
+    char err_text[160] = "";
+
+    StreamedRun(zi_engine* e_, int64_t n_uses_)
+        : e(e_), src(e_->src), segs(e_->segs), use_begin(e_->use_begin), n_uses(n_uses_), n_h(e_->n_hslots)
+    {
     }
-
-    // Overflow flag first: a skipped step moves nothing (4 bytes decide about gigabytes of traffic).
-    if (d_norm) {
-        ZI_HIP(hipMemcpyAsync(e->h_norm, d_norm, sizeof(zi_norm_result), hipMemcpyDeviceToHost, user));
-        ZI_HIP(hipStreamSynchronize(user));
-        if (e->h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
-    }
-
-    // Everything already enqueued on the caller's stream (gradients, norm) happens before our work.
-    ZI_HIP(hipEventRecord(e->ev_in, user));
-    ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
-    ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
-
-    const zi::StepConsts k = make_consts(*cfg);
-    const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
-    const int n_h = e->n_hslots;
-
-    // First segment of every slot use.
-    std::vector<size_t> use_begin((size_t)n_uses + 1, segs.size());
-    for (size_t j = segs.size(); j-- > 0;) use_begin[(size_t)segs[j].slot_use] = j;
-    for (int64_t u = n_uses - 1; u >= 0; --u)
-        if (use_begin[(size_t)u] > use_begin[(size_t)u + 1]) use_begin[(size_t)u] = use_begin[(size_t)u + 1];
 
     // Where a segment sits inside a slot (HBM slot and pinned-ring slot share one layout).
-    auto slot_off = [&](const Segment& sg) -> int64_t {
+    int64_t slot_off(const Segment& sg) const
+    {
         // Lead-in elements that give the staged arrays the alignment phase of the device-resident
         // 2-byte array the kernel will see beside them (gradients, else the low-precision copy).
         const StateSrc& S = src[(size_t)sg.tensor];
@@ -336,30 +269,31 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
         if (!S.g_host) ref = (const uint16_t*)S.g + sg.elem_offset;
         else if (S.p_lp && !S.lp_host) ref = (const uint16_t*)S.p_lp + sg.elem_offset;
         return sg.slot_offset + (ref ? (int64_t)((reinterpret_cast<uintptr_t>(ref) / 2) % 4) : 0);
-    };
+    }
+
     // Transfer lists between the caller's state (ordinary memory or files) and ring slot h for one
     // slot use.  Direct-I/O files move whole 4096-byte blocks: the rounded-up tail of a region is read
     // and written back unchanged (the update only touches `count` elements of the slot).
-    auto ring_pieces = [&](int64_t use, int h, bool inbound, std::vector<CopyPool::Piece>& out) {
+    void ring_pieces(int64_t use, int h, bool inbound, std::vector<Piece>& out) const
+    {
         out.clear();
+        auto mem_pieces = [&](char* ring, char* user_mem, size_t bytes) {
+            for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
+                const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
+                if (inbound) out.push_back({0, ring + o, user_mem + o, -1, 0, nb, nb, false});
+                else         out.push_back({0, user_mem + o, ring + o, -1, 0, nb, nb, false});
+            }
+        };
         for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
             const Segment& sg = segs[j];
             const StateSrc& S = src[(size_t)sg.tensor];
-            auto mem_pieces = [&](char* ring, char* user_mem, size_t bytes) {
-                for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
-                    const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
-                    if (inbound) out.push_back({0, ring + o, user_mem + o, -1, 0, nb, nb, false});
-                    else         out.push_back({0, user_mem + o, ring + o, -1, 0, nb, nb, false});
-                }
-            };
+            const int64_t so = slot_off(sg);
             if (inbound && S.g_host)
-                mem_pieces((char*)(e->hslot_g(h) + slot_off(sg)), (char*)S.g + sg.elem_offset * 2,
-                           (size_t)sg.count * 2);
+                mem_pieces((char*)(e->hslot_g(h) + so), (char*)S.g + sg.elem_offset * 2, (size_t)sg.count * 2);
             if (!inbound && S.lp_host && S.p_lp)
-                mem_pieces((char*)(e->hslot_lp(h) + slot_off(sg)), (char*)S.p_lp + sg.elem_offset * 2,
-                           (size_t)sg.count * 2);
+                mem_pieces((char*)(e->hslot_lp(h) + so), (char*)S.p_lp + sg.elem_offset * 2, (size_t)sg.count * 2);
             for (int w = 0; w < 3; ++w) {
-                char* rp = (char*)(e->hslot_array(h, w) + slot_off(sg));
+                char* rp = (char*)(e->hslot_array(h, w) + so);
                 const size_t need = (size_t)sg.count * 4;
                 if (S.kind == kSrcFile) {
                     const size_t total = S.direct[w] ? (need + 4095) / 4096 * 4096 : need;
@@ -370,99 +304,129 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
                         out.push_back({inbound ? 1 : 2, rp + o, nullptr, S.fd[w], fo + (int64_t)o, nb, nd, S.direct[w]});
                     }
                 } else {
-                    char* up = S.ptr[w] + sg.elem_offset * 4;
-                    for (size_t o = 0; o < need; o += kCopyPieceBytes) {
-                        const size_t nb = need - o < kCopyPieceBytes ? need - o : kCopyPieceBytes;
-                        if (inbound) out.push_back({0, rp + o, up + o, -1, 0, nb, nb, false});
-                        else         out.push_back({0, up + o, rp + o, -1, 0, nb, nb, false});
-                    }
+                    mem_pieces(rp, S.ptr[w] + sg.elem_offset * 4, need);
                 }
             }
         }
-    };
+    }
 
-    // Progress shared by the three actors of the ring path (gather thread, this thread, scatter thread).
-    struct {
-        std::mutex mu;
-        std::condition_variable cv;
-        int64_t gathered = 0, issued = 0, scattered = 0;
-        bool abort = false;
-        bool io_error = false;
-        char scatter_err[160] = "";
-    } sync;
-    uint64_t staged_bytes = 0;
-    std::thread gather_thread, scatter_thread;
-    auto stop_threads = [&] {
-        {
-            std::lock_guard<std::mutex> lk(sync.mu);
-            sync.abort = true;
-        }
-        sync.cv.notify_all();
-        if (gather_thread.joinable()) gather_thread.join();
-        if (scatter_thread.joinable()) scatter_thread.join();
-    };
-    if (staged) try {
-        gather_thread = std::thread([&] {
-            std::vector<CopyPool::Piece> pieces;
-            for (int64_t u = 0; u < n_uses; ++u) {
+    void fail_stage(const char* what, const char* detail, bool io)
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        if (!abort) snprintf(err_text, sizeof err_text, "%s: %s", what, detail);
+        abort = true;
+        io_error = io_error || io;
+    }
+
+    // Stage thread: fills ring slot u mod n_h with the state of slot use u, as soon as the slot's
+    // previous contents have been written back.
+    static void gather_main(void* ctx)
+    {
+        StreamedRun& r = *static_cast<StreamedRun*>(ctx);
+        try {
+            for (int64_t u = 0; u < r.n_uses; ++u) {
                 {
-                    std::unique_lock<std::mutex> lk(sync.mu);
-                    sync.cv.wait(lk, [&] { return sync.abort || sync.scattered >= u - n_h + 1; });
-                    if (sync.abort) return;
+                    std::unique_lock<std::mutex> lk(r.mu);
+                    r.cv.wait(lk, [&] { return r.abort || r.scattered >= u - r.n_h + 1; });
+                    if (r.abort) return;
                 }
-                ring_pieces(u, (int)(u % n_h), true, pieces);
-                const int err = e->pool_in->run(pieces);
-                {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    if (err) {
-                        snprintf(sync.scatter_err, sizeof sync.scatter_err, "reading state: %s", strerror(err));
-                        sync.abort = sync.io_error = true;
-                    } else {
-                        sync.gathered = u + 1;
-                    }
-                }
-                sync.cv.notify_all();
-                if (err) return;
-            }
-        });
-        scatter_thread = std::thread([&] {
-            (void)hipSetDevice(e->device);
-            std::vector<CopyPool::Piece> pieces;
-            for (int64_t u = 0; u < n_uses; ++u) {
-                {
-                    std::unique_lock<std::mutex> lk(sync.mu);
-                    sync.cv.wait(lk, [&] { return sync.abort || sync.issued > u; });
-                    if (sync.abort) return;
-                }
-                const int h = (int)(u % n_h);
-                hipError_t he = hipEventSynchronize(e->ev_back[h]);
-                if (he != hipSuccess) {
-                    (void)hipGetLastError();
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    snprintf(sync.scatter_err, sizeof sync.scatter_err, "hipEventSynchronize: %s",
-                             hipGetErrorString(he));
-                    sync.abort = true;
-                    sync.cv.notify_all();
+                r.ring_pieces(u, (int)(u % r.n_h), true, r.e->pieces_in);
+                const int err = run_pieces(*r.e->pool_in, r.e->pieces_in);
+                if (err) {
+                    r.fail_stage("reading state", strerror(err), true);
+                    r.cv.notify_all();
                     return;
                 }
-                ring_pieces(u, h, false, pieces);
-                const int err = e->pool_out->run(pieces);
                 {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    if (err) {
-                        snprintf(sync.scatter_err, sizeof sync.scatter_err, "writing state: %s", strerror(err));
-                        sync.abort = sync.io_error = true;
-                    } else {
-                        sync.scattered = u + 1;
-                    }
+                    std::lock_guard<std::mutex> lk(r.mu);
+                    r.gathered = u + 1;
                 }
-                sync.cv.notify_all();
-                if (err) return;
+                r.cv.notify_all();
             }
-        });
-    } catch (const std::exception& ex) {
-        stop_threads();
-        return fail(ZI_ERR_NOMEM, "could not start the ring's copy threads: %s", ex.what());
+        } catch (const std::exception& ex) {
+            r.fail_stage("reading state", ex.what(), false);
+            r.cv.notify_all();
+        }
+    }
+
+    // Stage thread: once the device-to-host copies of slot use u have landed in its ring slot, writes
+    // the slot back to the caller's state.
+    static void scatter_main(void* ctx)
+    {
+        StreamedRun& r = *static_cast<StreamedRun*>(ctx);
+        try {
+            (void)hipSetDevice(r.e->device);
+            for (int64_t u = 0; u < r.n_uses; ++u) {
+                {
+                    std::unique_lock<std::mutex> lk(r.mu);
+                    r.cv.wait(lk, [&] { return r.abort || r.issued > u; });
+                    if (r.abort) return;
+                }
+                const int h = (int)(u % r.n_h);
+                const hipError_t he = hipEventSynchronize(r.e->ev_back[h]);
+                if (he != hipSuccess) {
+                    (void)hipGetLastError();
+                    r.fail_stage("hipEventSynchronize", hipGetErrorString(he), false);
+                    r.cv.notify_all();
+                    return;
+                }
+                r.ring_pieces(u, h, false, r.e->pieces_out);
+                const int err = run_pieces(*r.e->pool_out, r.e->pieces_out);
+                if (err) {
+                    r.fail_stage("writing state", strerror(err), true);
+                    r.cv.notify_all();
+                    return;
+                }
+                {
+                    std::lock_guard<std::mutex> lk(r.mu);
+                    r.scattered = u + 1;
+                }
+                r.cv.notify_all();
+            }
+        } catch (const std::exception& ex) {
+            r.fail_stage("writing state", ex.what(), false);
+            r.cv.notify_all();
+        }
+    }
+};
+
+zi_status run_streamed(zi_engine* e, bool staged, zi_lp_dtype dt, const zi_adamw_config* cfg,
+                       const zi_norm_result* d_norm, hipStream_t user)
+{
+    const std::vector<StateSrc>& src = e->src;
+    const int32_t n_tensors = (int32_t)src.size();
+    e->plan_numel.resize((size_t)n_tensors);
+    for (int32_t i = 0; i < n_tensors; ++i) e->plan_numel[(size_t)i] = src[(size_t)i].numel;
+    int64_t n_uses = 0;
+    plan_chunks(e->plan_numel.data(), n_tensors, e->chunk_elems, e->segs, n_uses);
+    index_uses(e->segs, n_uses, e->use_begin);
+    const std::vector<Segment>& segs = e->segs;
+    const std::vector<size_t>& use_begin = e->use_begin;
+
+    // Overflow flag first: a skipped step moves nothing (4 bytes decide about gigabytes of traffic).
+    if (d_norm) {
+        ZI_HIP(hipMemcpyAsync(e->h_norm, d_norm, sizeof(zi_norm_result), hipMemcpyDeviceToHost, user));
+        ZI_HIP(hipStreamSynchronize(user));
+        if (e->h_norm->found_inf) return ZI_SKIPPED_OVERFLOW;
+    }
+
+    // Everything already enqueued on the caller's stream (gradients, norm) happens before our work,
+    // and so do gradient offloads still on their way to host memory.
+    ZI_HIP(hipEventRecord(e->ev_in, user));
+    ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
+    ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
+    ZI_HIP(order_after_offloads(e, e->s_h2d));
+    if (staged && e->offload_pending) ZI_HIP(hipEventSynchronize(e->ev_offload_done));   // CPU threads read host memory
+
+    const zi::StepConsts k = make_consts(*cfg);
+    const bool l2 = cfg->mode == ZI_MODE_ADAM_L2;
+    const int n_h = e->n_hslots;
+
+    StreamedRun run(e, n_uses);
+    uint64_t staged_bytes = 0;
+    if (staged) {
+        e->stage_in->start(&StreamedRun::gather_main, &run);
+        e->stage_out->start(&StreamedRun::scatter_main, &run);
     }
 
     const auto t0 = std::chrono::steady_clock::now();
@@ -472,9 +436,9 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
             const int slot = (int)(use % e->n_slots);
             const int h = staged ? (int)(use % n_h) : 0;
             if (staged) {
-                std::unique_lock<std::mutex> lk(sync.mu);
-                sync.cv.wait(lk, [&] { return sync.abort || sync.gathered > use; });
-                if (sync.abort) return fail(sync.io_error ? ZI_ERR_IO : ZI_ERR_HIP, "%s", sync.scatter_err);
+                std::unique_lock<std::mutex> lk(run.mu);
+                run.cv.wait(lk, [&] { return run.abort || run.gathered > use; });
+                if (run.abort) return fail(run.io_error ? ZI_ERR_IO : ZI_ERR_HIP, "%s", run.err_text);
             }
             // Slot reuse is ordered by the event of the device-to-host copies that last emptied it.
             // The host waits for the use `depth` positions back before it issues this one.  Depth 2
@@ -492,7 +456,7 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
             for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j, ++np) {
                 const Segment& sg = segs[j];
                 const StateSrc& T = src[(size_t)sg.tensor];
-                const int64_t so = slot_off(sg);
+                const int64_t so = run.slot_off(sg);
                 Placed& P = placed[np];
                 P.dp = e->slot_array(slot, 0) + so;
                 P.dm = e->slot_array(slot, 1) + so;
@@ -567,10 +531,10 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
             if (staged) {
                 ZI_HIP(hipEventRecord(e->ev_back[h], e->s_d2h));
                 {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    sync.issued = use + 1;
+                    std::lock_guard<std::mutex> lk(run.mu);
+                    run.issued = use + 1;
                 }
-                sync.cv.notify_all();
+                run.cv.notify_all();
             }
             ++e->stats.n_slot_uses;
         }
@@ -586,14 +550,15 @@ zi_status run_streamed(zi_engine* e, const std::vector<StateSrc>& src, bool stag
     if (st != ZI_OK) drain_streams(e);     // nothing of ours still touches the caller's memory on return
     if (staged) {
         if (st != ZI_OK) {
-            std::lock_guard<std::mutex> lk(sync.mu);
-            sync.abort = true;
+            std::lock_guard<std::mutex> lk(run.mu);
+            run.abort = true;
         }
-        sync.cv.notify_all();
-        gather_thread.join();
-        scatter_thread.join();
-        if (st == ZI_OK && sync.abort) st = fail(sync.io_error ? ZI_ERR_IO : ZI_ERR_HIP, "%s", sync.scatter_err);
+        run.cv.notify_all();
+        e->stage_in->wait();
+        e->stage_out->wait();
+        if (st == ZI_OK && run.abort) st = fail(run.io_error ? ZI_ERR_IO : ZI_ERR_HIP, "%s", run.err_text);
     }
+    if (st == ZI_OK) e->offload_pending = false;      // every stream that carried an offload has been drained
     e->stats.bytes_staged_host = staged_bytes;
     e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return st;
@@ -605,6 +570,7 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
                                             const zi_adamw_config* cfg, const zi_norm_result* d_norm,
                                             void* hip_stream)
 {
+    ZI_GUARD_BEGIN
     if (zi_status st = check_engine(e)) return st;
     if (zi_status st = check_dtype((int)dt)) return st;
     if (zi_status st = check_config(cfg)) return st;
@@ -621,9 +587,10 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
     // has been set up, otherwise it is refused.  Gradients and the low-precision copy may live on
     // the device (used in place) or in host memory (staged with the state, chunk by chunk).
     bool pageable = false;
-    std::vector<StateSrc> src((size_t)n_tensors);
+    PointerChecker reach;
+    e->src.resize((size_t)n_tensors);
     for (int32_t i = 0; i < n_tensors; ++i) {
-        StateSrc& S = src[(size_t)i];
+        StateSrc& S = e->src[(size_t)i];
         S.kind = kSrcPinned;
         S.ptr[0] = (char*)t[i].p; S.ptr[1] = (char*)t[i].m; S.ptr[2] = (char*)t[i].v;
         S.fd[0] = S.fd[1] = S.fd[2] = -1;
@@ -632,18 +599,20 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
         S.g = t[i].g; S.p_lp = t[i].p_lp; S.numel = t[i].numel;
         S.g_host = S.lp_host = false;
         if (t[i].numel == 0) continue;
+        const size_t n = (size_t)t[i].numel;
+        static const char* const names[3] = {"p", "m", "v"};
         for (int w = 0; w < 3; ++w) {
-            const int kind = memory_kind(S.ptr[w]);
-            if (kind != 1 && kind != 2) return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be host memory", i);
+            int kind = 0;
+            if (zi_status st = classify_array(reach, S.ptr[w], n * 4, i, names[w], kind)) return st;
+            if (kind == 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: p, m, v must be host memory", i);
             if (kind == 2) pageable = true;
         }
-        const int gk = memory_kind(S.g);
-        if (gk < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is neither device nor host memory", i);
+        int gk = 0, lk = 0;
+        if (zi_status st = classify_array(reach, S.g, n * 2, i, "g", gk)) return st;
         S.g_host = gk != 0;
         if (gk == 2) pageable = true;
         if (S.p_lp) {
-            const int lk = memory_kind(S.p_lp);
-            if (lk < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: p_lp is neither device nor host memory", i);
+            if (zi_status st = classify_array(reach, S.p_lp, n * 2, i, "p_lp", lk)) return st;
             S.lp_host = lk != 0;
             if (lk == 2) pageable = true;
         }
@@ -652,15 +621,94 @@ extern "C" zi_status zi_adamw_step_streamed(zi_engine* e, const zi_tensor* t, in
         if (e->n_hslots == 0)
             return fail(ZI_ERR_INVALID_ARG, "host arrays must be pinned host memory (or give the engine a pinned "
                                             "ring with ZI_OPT_HOST_RING_SLOTS)");
-        for (auto& S : src) S.kind = kSrcPageable;   // one path per call: everything host-side rides the ring
+        for (auto& S : e->src) S.kind = kSrcPageable;   // one path per call: everything host-side rides the ring
     }
-    return run_streamed(e, src, pageable, dt, cfg, d_norm, user);
+    return run_streamed(e, pageable, dt, cfg, d_norm, user);
+    ZI_GUARD_END
 }
+
+namespace {
+
+// Shared state of zi_grad_norm_streamed's ring path: one stage thread fills ring slots with chunks
+// of host-resident gradients, the caller's thread ships them to HBM and reduces them.
+struct NormRun {
+    zi_engine* e;
+    const zi_tensor* t;
+    int64_t n_uses;
+    int n_h;
+    std::mutex mu;
+    std::condition_variable cv;
+    int64_t gathered = 0, issued = 0;
+    bool abort = false;
+    char err_text[160] = "";
+
+    void fail_stage(const char* what, const char* detail)
+    {
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            if (!abort) snprintf(err_text, sizeof err_text, "%s: %s", what, detail);
+            abort = true;
+        }
+        cv.notify_all();
+    }
+
+    static void gather_main(void* ctx)
+    {
+        NormRun& r = *static_cast<NormRun*>(ctx);
+        zi_engine* e = r.e;
+        try {
+            (void)hipSetDevice(e->device);
+            for (int64_t u = 0; u < r.n_uses; ++u) {
+                const int h = (int)(u % r.n_h);
+                if (u >= r.n_h) {      // the ring slot is free once its previous host-to-device copies are done
+                    {
+                        std::unique_lock<std::mutex> lk(r.mu);
+                        r.cv.wait(lk, [&] { return r.abort || r.issued > u - r.n_h; });
+                        if (r.abort) return;
+                    }
+                    const hipError_t he = hipEventSynchronize(e->ev_back[h]);
+                    if (he != hipSuccess) {
+                        (void)hipGetLastError();
+                        r.fail_stage("hipEventSynchronize", hipGetErrorString(he));
+                        return;
+                    }
+                }
+                std::vector<Piece>& pieces = e->pieces_in;
+                pieces.clear();
+                for (size_t j = e->use_begin[(size_t)u]; j < e->use_begin[(size_t)u + 1]; ++j) {
+                    const Segment& sg = e->segs[j];
+                    char* ring = (char*)(e->hslot_g(h) + sg.slot_offset);
+                    const char* um = (const char*)r.t[e->host_idx[(size_t)sg.tensor]].g + sg.elem_offset * 2;
+                    const size_t bytes = (size_t)sg.count * 2;
+                    for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
+                        const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
+                        pieces.push_back({0, ring + o, um + o, -1, 0, nb, nb, false});
+                    }
+                }
+                const int err = run_pieces(*e->pool_in, pieces);
+                if (err) {
+                    r.fail_stage("copying gradients into the pinned ring", strerror(err));
+                    return;
+                }
+                {
+                    std::lock_guard<std::mutex> lk(r.mu);
+                    r.gathered = u + 1;
+                }
+                r.cv.notify_all();
+            }
+        } catch (const std::exception& ex) {
+            r.fail_stage("copying gradients into the pinned ring", ex.what());
+        }
+    }
+};
+
+}  // namespace
 
 extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                                            float loss_scale, zi_norm_result* d_out, void* d_workspace,
                                            size_t workspace_bytes, void* hip_stream)
 {
+    ZI_GUARD_BEGIN
     if (zi_status st = check_engine(e)) return st;
     if (zi_status st = check_norm_args(t, n_tensors, (int)dt, loss_scale, d_out, d_workspace, workspace_bytes)) return st;
     if (zi_status st = check_kernel_visible(d_out, sizeof(zi_norm_result), -1, "d_out")) return st;
@@ -670,86 +718,41 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
     e->stats = zi_stream_stats{};
 
     // Device-resident gradients are reduced in place; host-resident ones are staged chunk by chunk.
-    std::vector<int32_t> host_idx;
-    std::vector<int64_t> host_numel;
+    e->host_idx.clear();
+    e->plan_numel.clear();
     bool pageable = false;
+    PointerChecker reach;
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (t[i].numel == 0) continue;
-        const int k = memory_kind(t[i].g);
-        if (k < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is neither device nor host memory", i);
+        int k = 0;
+        if (zi_status st = classify_array(reach, t[i].g, (size_t)t[i].numel * 2, i, "g", k)) return st;
         if (k == 0) continue;
         if (k == 2) pageable = true;
-        host_idx.push_back(i);
-        host_numel.push_back(t[i].numel);
+        e->host_idx.push_back(i);
+        e->plan_numel.push_back(t[i].numel);
     }
     if (pageable && e->n_hslots == 0)
         return fail(ZI_ERR_INVALID_ARG, "host gradients must be pinned host memory (or give the engine a pinned "
                                         "ring with ZI_OPT_HOST_RING_SLOTS)");
-    std::vector<Segment> segs;
     int64_t n_uses = 0;
-    try {
-        plan_chunks(host_numel.data(), (int32_t)host_numel.size(), e->chunk_elems, segs, n_uses);
-    } catch (const std::bad_alloc&) {
-        return fail(ZI_ERR_NOMEM, "out of host memory while planning");
-    }
-    std::vector<size_t> use_begin((size_t)n_uses + 1, segs.size());
-    for (size_t j = segs.size(); j-- > 0;) use_begin[(size_t)segs[j].slot_use] = j;
-    for (int64_t u = n_uses - 1; u >= 0; --u)
-        if (use_begin[(size_t)u] > use_begin[(size_t)u + 1]) use_begin[(size_t)u] = use_begin[(size_t)u + 1];
+    plan_chunks(e->plan_numel.data(), (int32_t)e->plan_numel.size(), e->chunk_elems, e->segs, n_uses);
+    index_uses(e->segs, n_uses, e->use_begin);
+    const std::vector<Segment>& segs = e->segs;
+    const std::vector<size_t>& use_begin = e->use_begin;
 
     ZI_HIP(hipEventRecord(e->ev_in, user));
     ZI_HIP(hipStreamWaitEvent(e->s_h2d, e->ev_in, 0));
     ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_in, 0));
+    ZI_HIP(order_after_offloads(e, e->s_h2d));
+    if (pageable && e->offload_pending) ZI_HIP(hipEventSynchronize(e->ev_offload_done));
 
     const int n_h = e->n_hslots;
-    struct {
-        std::mutex mu;
-        std::condition_variable cv;
-        int64_t gathered = 0, issued = 0;
-        bool abort = false;
-    } sync;
-    std::thread gather_thread;
-    if (pageable) try {
-        gather_thread = std::thread([&] {
-            (void)hipSetDevice(e->device);
-            std::vector<CopyPool::Piece> pieces;
-            for (int64_t u = 0; u < n_uses; ++u) {
-                const int h = (int)(u % n_h);
-                if (u >= n_h) {      // the ring slot is free once its previous host-to-device copies are done
-                    std::unique_lock<std::mutex> lk(sync.mu);
-                    sync.cv.wait(lk, [&] { return sync.abort || sync.issued > u - n_h; });
-                    if (sync.abort) return;
-                    lk.unlock();
-                    if (hipEventSynchronize(e->ev_back[h]) != hipSuccess) {
-                        (void)hipGetLastError();
-                        std::lock_guard<std::mutex> lk2(sync.mu);
-                        sync.abort = true;
-                        sync.cv.notify_all();
-                        return;
-                    }
-                }
-                pieces.clear();
-                for (size_t j = use_begin[(size_t)u]; j < use_begin[(size_t)u + 1]; ++j) {
-                    const Segment& sg = segs[j];
-                    char* ring = (char*)(e->hslot_g(h) + sg.slot_offset);
-                    const char* um = (const char*)t[host_idx[(size_t)sg.tensor]].g + sg.elem_offset * 2;
-                    const size_t bytes = (size_t)sg.count * 2;
-                    for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
-                        const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
-                        pieces.push_back({0, ring + o, um + o, -1, 0, nb, nb, false});
-                    }
-                }
-                e->pool_in->run(pieces);
-                {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    sync.gathered = u + 1;
-                }
-                sync.cv.notify_all();
-            }
-        });
-    } catch (const std::exception& ex) {
-        return fail(ZI_ERR_NOMEM, "could not start the ring's copy thread: %s", ex.what());
-    }
+    NormRun run;
+    run.e = e;
+    run.t = t;
+    run.n_uses = n_uses;
+    run.n_h = n_h;
+    if (pageable) e->stage_in->start(&NormRun::gather_main, &run);
 
     const auto t0 = std::chrono::steady_clock::now();
     uint64_t staged_bytes = 0;
@@ -761,16 +764,16 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
             const int slot = (int)(use % e->n_slots);
             const int h = pageable ? (int)(use % n_h) : 0;
             if (pageable) {
-                std::unique_lock<std::mutex> lk(sync.mu);
-                sync.cv.wait(lk, [&] { return sync.abort || sync.gathered > use; });
-                if (sync.abort) return fail(ZI_ERR_HIP, "waiting for the pinned ring failed");
+                std::unique_lock<std::mutex> lk(run.mu);
+                run.cv.wait(lk, [&] { return run.abort || run.gathered > use; });
+                if (run.abort) return fail(ZI_ERR_HIP, "%s", run.err_text);
             }
             // the slot's staged gradients are free once the reduction that last read them is done
             if (use >= e->n_slots) ZI_HIP(hipEventSynchronize(e->ev_k[slot]));
             for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j) {
                 const Segment& sg = segs[j];
                 const char* hg = pageable ? (const char*)(e->hslot_g(h) + sg.slot_offset)
-                                          : (const char*)t[host_idx[(size_t)sg.tensor]].g + sg.elem_offset * 2;
+                                          : (const char*)t[e->host_idx[(size_t)sg.tensor]].g + sg.elem_offset * 2;
                 ZI_HIP(hipMemcpyAsync(e->slot_g(slot) + sg.slot_offset, hg, (size_t)sg.count * 2,
                                       hipMemcpyHostToDevice, e->s_h2d));
                 e->stats.bytes_h2d += (size_t)sg.count * 2;
@@ -781,10 +784,10 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
             if (pageable) {
                 ZI_HIP(hipEventRecord(e->ev_back[h], e->s_h2d));
                 {
-                    std::lock_guard<std::mutex> lk(sync.mu);
-                    sync.issued = use + 1;
+                    std::lock_guard<std::mutex> lk(run.mu);
+                    run.issued = use + 1;
                 }
-                sync.cv.notify_all();
+                run.cv.notify_all();
             }
             ZI_HIP(hipStreamWaitEvent(e->s_k, e->ev_h2d[slot], 0));
             for (size_t j = use_begin[(size_t)use]; j < use_begin[(size_t)use + 1]; ++j)
@@ -804,22 +807,24 @@ extern "C" zi_status zi_grad_norm_streamed(zi_engine* e, const zi_tensor* t, int
     if (st != ZI_OK) drain_streams(e);
     if (pageable) {
         if (st != ZI_OK) {
-            std::lock_guard<std::mutex> lk(sync.mu);
-            sync.abort = true;
+            std::lock_guard<std::mutex> lk(run.mu);
+            run.abort = true;
         }
-        sync.cv.notify_all();
-        gather_thread.join();
-        if (st == ZI_OK && sync.abort) st = fail(ZI_ERR_HIP, "the pinned ring's copy thread failed");
+        run.cv.notify_all();
+        e->stage_in->wait();
+        if (st == ZI_OK && run.abort) st = fail(ZI_ERR_HIP, "%s", run.err_text);
     }
     e->stats.bytes_staged_host = staged_bytes;
     e->stats.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     return st;
+    ZI_GUARD_END
 }
 
 extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, int32_t n_tensors, zi_lp_dtype dt,
                                          const zi_adamw_config* cfg, const zi_norm_result* d_norm,
                                          void* hip_stream)
 {
+    ZI_GUARD_BEGIN
     if (zi_status st = check_engine(e)) return st;
     if (zi_status st = check_dtype((int)dt)) return st;
     if (zi_status st = check_config(cfg)) return st;
@@ -830,9 +835,10 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
     if (e->n_hslots == 0)
         return fail(ZI_ERR_INVALID_ARG, "file-resident state needs a pinned ring (ZI_OPT_HOST_RING_SLOTS)");
 
-    std::vector<StateSrc> src((size_t)n_tensors);
+    PointerChecker reach;
+    e->src.resize((size_t)n_tensors);
     for (int32_t i = 0; i < n_tensors; ++i) {
-        StateSrc& S = src[(size_t)i];
+        StateSrc& S = e->src[(size_t)i];
         S.kind = kSrcFile;
         S.ptr[0] = S.ptr[1] = S.ptr[2] = nullptr;
         S.fd[0] = t[i].fd_p; S.fd[1] = t[i].fd_m; S.fd[2] = t[i].fd_v;
@@ -844,8 +850,10 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
         if (!S.g) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g is NULL", i);
         if (!aligned(S.g, 2) || !aligned(S.p_lp, 2))
             return fail(ZI_ERR_ALIGNMENT, "tensor %d: g and p_lp must be 2-byte aligned", i);
-        const int gk = memory_kind(S.g), lk = S.p_lp ? memory_kind(S.p_lp) : 0;
-        if (gk < 0 || lk < 0) return fail(ZI_ERR_INVALID_ARG, "tensor %d: g / p_lp is neither device nor host memory", i);
+        int gk = 0, lk = 0;
+        if (zi_status st = classify_array(reach, S.g, (size_t)S.numel * 2, i, "g", gk)) return st;
+        if (S.p_lp)
+            if (zi_status st = classify_array(reach, S.p_lp, (size_t)S.numel * 2, i, "p_lp", lk)) return st;
         S.g_host = gk != 0;
         S.lp_host = S.p_lp && lk != 0;
         // the device-resident 2-byte array that sets the alignment phase of the staged arrays, if any
@@ -868,95 +876,6 @@ extern "C" zi_status zi_adamw_step_files(zi_engine* e, const zi_file_tensor* t, 
     }
     ZI_HIP(hipSetDevice(e->device));
     e->stats = zi_stream_stats{};
-    return run_streamed(e, src, true, dt, cfg, d_norm, (hipStream_t)hip_stream);
+    return run_streamed(e, true, dt, cfg, d_norm, (hipStream_t)hip_stream);
+    ZI_GUARD_END
 }
-
-extern "C" zi_status zi_engine_file_probe(zi_engine* e, int32_t fd_read, int32_t fd_write, size_t bytes,
-                                          double* seconds_out)
-{
-    if (zi_status st = check_engine(e)) return st;
-    if (!seconds_out) return fail(ZI_ERR_INVALID_ARG, "seconds_out is NULL");
-    if (e->n_hslots == 0) return fail(ZI_ERR_INVALID_ARG, "the probe needs a pinned ring (ZI_OPT_HOST_RING_SLOTS)");
-    if (fd_read < 0 && fd_write < 0) return fail(ZI_ERR_INVALID_ARG, "no file descriptor given");
-    if (bytes == 0 || bytes % 4096) return fail(ZI_ERR_INVALID_ARG, "bytes must be a positive multiple of 4096");
-    if (e->n_hslots < 2) return fail(ZI_ERR_INVALID_ARG, "ring too small");
-    // Reads land in the first half of the ring, writes leave from the second half.
-    const size_t half = (size_t)(e->n_hslots / 2) * kSlotArrays * e->array_bytes / 4096 * 4096;
-    auto pieces_for = [&](int fd, int op, char* base, std::vector<CopyPool::Piece>& out) {
-        const int fl = fcntl(fd, F_GETFL);
-        const bool direct = fl >= 0 && (fl & O_DIRECT);
-        size_t ring_o = 0;
-        for (size_t o = 0; o < bytes; o += kCopyPieceBytes) {
-            const size_t nb = bytes - o < kCopyPieceBytes ? bytes - o : kCopyPieceBytes;
-            if (ring_o + nb > half) ring_o = 0;
-            out.push_back({op, base + ring_o, nullptr, fd, (int64_t)o, nb, nb, direct});
-            ring_o += nb;
-        }
-    };
-    std::vector<CopyPool::Piece> rd, wr;
-    if (fd_read >= 0) pieces_for(fd_read, 1, e->hring, rd);
-    if (fd_write >= 0) pieces_for(fd_write, 2, e->hring + half, wr);
-    int err_r = 0, err_w = 0;
-    const auto t0 = std::chrono::steady_clock::now();
-    std::thread tw;
-    if (!wr.empty()) tw = std::thread([&] { err_w = e->pool_out->run(wr); });
-    if (!rd.empty()) err_r = e->pool_in->run(rd);
-    if (tw.joinable()) tw.join();
-    *seconds_out = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
-    if (err_r) return fail(ZI_ERR_IO, "reading: %s", strerror(err_r));
-    if (err_w) return fail(ZI_ERR_IO, "writing: %s", strerror(err_w));
-    return ZI_OK;
-}
-
-extern "C" zi_status zi_engine_link_probe(zi_engine* e, const void* host_src, void* host_dst, size_t bytes,
-                                          int32_t mode, int32_t repeats, double* seconds_out)
-{
-    if (zi_status st = check_engine(e)) return st;
-    if (mode < 0 || mode > 2) return fail(ZI_ERR_INVALID_ARG, "mode must be 0, 1 or 2");
-    if (repeats < 1) return fail(ZI_ERR_INVALID_ARG, "repeats < 1");
-    if (!seconds_out) return fail(ZI_ERR_INVALID_ARG, "seconds_out is NULL");
-    if ((mode == 0 || mode == 2) && !host_src) return fail(ZI_ERR_INVALID_ARG, "host_src is NULL");
-    if ((mode == 1 || mode == 2) && !host_dst) return fail(ZI_ERR_INVALID_ARG, "host_dst is NULL");
-    if (bytes == 0) return fail(ZI_ERR_INVALID_ARG, "bytes is 0");
-    ZI_HIP(hipSetDevice(e->device));
-    ZI_HIP(hipStreamSynchronize(e->s_h2d));
-    ZI_HIP(hipStreamSynchronize(e->s_d2h));
-
-    // Host-to-device pieces land in the p arrays of the slots, device-to-host pieces leave from
-    // the m arrays, so the two directions never touch the same staging bytes.  In the two-way mode
-    // the host keeps the same number of pieces in flight as the streamed step does (a deep queue
-    // lets one direction run ahead and measures a lower two-way rate).
-    const int depth = e->max_inflight < e->n_slots ? e->max_inflight : e->n_slots;
-    const auto t0 = std::chrono::steady_clock::now();
-    for (int r = 0; r < repeats; ++r) {
-        int64_t piece = 0;
-        for (size_t off = 0; off < bytes; off += e->chunk_bytes, ++piece) {
-            const size_t nb = bytes - off < e->chunk_bytes ? bytes - off : e->chunk_bytes;
-            const int slot = (int)(piece % e->n_slots);
-            if (mode == 2 && piece >= depth) {
-                const int old_slot = (int)((piece - depth) % e->n_slots);
-                ZI_HIP(hipEventSynchronize(e->ev_h2d[old_slot]));
-                ZI_HIP(hipEventSynchronize(e->ev_d2h[old_slot]));
-            }
-            if (mode == 0 || mode == 2)
-                ZI_HIP(hipMemcpyAsync(e->slot_array(slot, 0), (const char*)host_src + off, nb,
-                                      hipMemcpyHostToDevice, e->s_h2d));
-            if (mode == 1 || mode == 2)
-                ZI_HIP(hipMemcpyAsync((char*)host_dst + off, e->slot_array(slot, 1), nb, hipMemcpyDeviceToHost,
-                                      e->s_d2h));
-            if (mode == 2) {
-                ZI_HIP(hipEventRecord(e->ev_h2d[slot], e->s_h2d));
-                ZI_HIP(hipEventRecord(e->ev_d2h[slot], e->s_d2h));
-            }
-        }
-        if (mode == 2) {     // the next repeat starts with an empty pipeline
-            ZI_HIP(hipStreamSynchronize(e->s_h2d));
-            ZI_HIP(hipStreamSynchronize(e->s_d2h));
-        }
-    }
-    ZI_HIP(hipStreamSynchronize(e->s_h2d));
-    ZI_HIP(hipStreamSynchronize(e->s_d2h));
-    *seconds_out = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
-    return ZI_OK;
-}
-

@@ -452,8 +452,15 @@ def test_copy_only_option_and_link_probe(engine):
     src = torch.zeros(1 << 20, dtype=torch.uint8, pin_memory=True)
     dst = torch.zeros(1 << 20, dtype=torch.uint8, pin_memory=True)
     for mode in (0, 1, 2):
-        sec = zi.zi_engine_link_probe(engine, src, dst, 1 << 20, mode, 2)
-        assert sec > 0
+        for piece, depth in ((0, 2), (4096, 0), (65536, 1), (1 << 18, 8)):
+            assert zi.zi_engine_link_probe(engine, src, dst, 1 << 20, mode, piece, depth) > 0
+    # what lands in host memory is the second half of the staging area: the probe moves real bytes
+    with pytest.raises(zi.ZiError):
+        zi.zi_engine_link_probe(engine, src, dst, 1 << 20, 2, 1 << 30, 2)          # piece beyond the staging memory
+    with pytest.raises(zi.ZiError):
+        zi.zi_engine_link_probe(engine, src, dst, 1 << 20, 2, 0, 9)
+    with pytest.raises(zi.ZiError):
+        zi.zi_engine_link_probe(engine, np.zeros(1 << 20, np.uint8), dst, 1 << 20, 0, 0, 2)   # pageable source
 
 
 def test_pinned_allocator_round_trip():
@@ -465,3 +472,186 @@ def test_pinned_allocator_round_trip():
 def test_engine_create_destroy_cycle():
     e = zi.zi_engine_create(0, 4096, 2)
     assert zi.zi_engine_destroy(e) == zi.ZI_OK
+
+
+# ------------------------------------------------------------------ gradient offload (device -> host)
+
+def test_gradient_partitions_drain_while_the_producer_keeps_running():
+    """Partitions of a gradient buffer are produced one after another on a producer stream (a dummy
+    producer: repeated device copies into the partition) and handed to zi_grad_offload as soon as they
+    are enqueued.  The calls return at once, the bytes arrive, and the total time shows that the drain
+    of partition k overlapped the production of partition k + 1."""
+    import time
+    part = 1 << 27                      # 128 MiB per partition: ~2.4 ms on the link
+    k_parts = 8
+    dev = "cuda:0"
+    src = torch.arange(part // 4, dtype=torch.int32, device=dev)
+    gbuf = torch.zeros(k_parts * part // 4, dtype=torch.int32, device=dev)
+    host = torch.zeros(k_parts * part // 4, dtype=torch.int32, pin_memory=True)
+    producer = torch.cuda.Stream()
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        def produce(k, reps):
+            view = gbuf[k * part // 4:(k + 1) * part // 4]
+            with torch.cuda.stream(producer):
+                for _ in range(reps):
+                    view.copy_(src)          # the last copy leaves the final value
+                view.add_(k)
+
+        # calibrate: production alone, offload alone
+        reps = 60
+        torch.cuda.synchronize()
+        t0 = time.perf_counter(); produce(0, reps); producer.synchronize(); t_prod = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        zi.zi_grad_offload(eng, gbuf, host, part, producer)
+        t_call = time.perf_counter() - t0
+        zi.zi_grad_offload_wait(eng)
+        t_copy = time.perf_counter() - t0
+        progress(f"offload: producing a partition {t_prod * 1e3:.2f} ms, draining it {t_copy * 1e3:.2f} ms, "
+                 f"the call itself {t_call * 1e6:.0f} us")
+        gbuf.zero_(); host.zero_()
+        torch.cuda.synchronize()
+
+        t0 = time.perf_counter()
+        calls = []
+        for k in range(k_parts):
+            produce(k, reps)
+            c0 = time.perf_counter()
+            zi.zi_grad_offload(eng, gbuf[k * part // 4:], host[k * part // 4:], part, producer)
+            calls.append(time.perf_counter() - c0)
+        producer.synchronize()
+        t_produced = time.perf_counter() - t0
+        zi.zi_grad_offload_wait(eng)
+        t_all = time.perf_counter() - t0
+        serial = k_parts * (t_prod + t_copy)
+        progress(f"offload: {k_parts} partitions produced in {t_produced * 1e3:.1f} ms, all on the host after "
+                 f"{t_all * 1e3:.1f} ms; one after the other would be {serial * 1e3:.1f} ms; slowest call "
+                 f"{max(calls) * 1e6:.0f} us")
+        assert max(calls) < 0.5 * min(t_prod, t_copy), "zi_grad_offload blocked"
+        assert t_all < 0.8 * serial, "the drain did not overlap the producer"
+        for k in range(k_parts):
+            want = (torch.arange(part // 4, dtype=torch.int32) + k)
+            assert torch.equal(host[k * part // 4:(k + 1) * part // 4], want), f"partition {k}"
+        # argument checks: pageable destination, host source
+        with pytest.raises(zi.ZiError):
+            zi.zi_grad_offload(eng, gbuf, np.zeros(16, np.int32), 64, producer)
+        with pytest.raises(zi.ZiError):
+            zi.zi_grad_offload(eng, host, host, 64, producer)
+        assert zi.zi_grad_offload(eng, gbuf, host, 0, producer) == zi.ZI_OK
+    finally:
+        zi.zi_engine_destroy(eng)
+
+
+def test_offloaded_gradients_feed_the_streamed_norm_and_step_without_a_host_wait():
+    """Gradients offloaded with zi_grad_offload are consumed from host memory by zi_grad_norm_streamed and
+    zi_adamw_step_streamed on the same engine with no wait in between: the engine orders itself after the
+    offload.  Results equal the oracle's."""
+    w = zi_synth.workload("c3")
+    dt = zi.ZI_FP16
+    n = 5 * 16384 + 77
+    p, m, v, g = gen_numpy(w["spec"], n)
+    d_g = to_dev(g)
+    hg = torch.zeros(n, dtype=torch.int16, pin_memory=True)
+    pp, pm, pv = (_pinned(a) for a in (p, m, v))
+    hlp = torch.zeros(n, dtype=torch.int16, pin_memory=True)
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        nb = NormBuffers()
+        zi.zi_grad_offload(eng, d_g, hg, 2 * n, torch.cuda.current_stream())
+        tl = [(pp, pm, pv, hg, hlp, n)]
+        zi.zi_grad_norm_streamed(eng, tl, dt, w["loss_scale"], nb.out, nb.ws)
+        st = zi.zi_adamw_step_streamed(eng, tl, dt, zi_cfg(w), nb.out)
+        assert st == zi.ZI_OK
+    finally:
+        zi.zi_engine_destroy(eng)
+    assert np.array_equal(hg.numpy().view(np.uint16), g)
+    sumsq, flag = oracle.grad_sumsq([g], dt)
+    lpe = np.zeros(n, np.uint16)
+    oracle.adamw(p, m, v, g, lpe, dt, oracle_cfg(w), sumsq, flag)
+    progress("offload -> streamed norm + step: " +
+             compare_state((p, m, v, lpe), (pp.numpy(), pm.numpy(), pv.numpy(), hlp.numpy().view(np.uint16)), dt))
+
+
+# ------------------------------------------------------ the step on the CPUs, link carries g and p_lp
+
+@pytest.mark.parametrize("dt", [zi.ZI_BF16, zi.ZI_FP16])
+@pytest.mark.parametrize("pinned", [True, False])
+def test_cpu_step_with_device_gradients_and_copy(dt, pinned):
+    """zi_adamw_step_cpu: state in host memory (pinned or ordinary), gradients and the copy on the device.
+    Bit-identical to zi_adamw_step_streamed on the same values and to the oracle; the link carried 2 + 2
+    bytes per element."""
+    w = zi_synth.workload("c4" if dt == zi.ZI_BF16 else "c3")
+    spec = zi_synth.StateSpec(777 + dt, dt, g_std=1e-3 if dt == zi.ZI_BF16 else 65.536)
+    sizes = [3 * 16384 + 5, 100, 16384, 0, 7, 2 * 16384 - 1, 40_000]
+    host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(sizes)]
+    kw = dict(max_grad_norm=0.02, loss_scale=1.0 if dt == zi.ZI_BF16 else 65536.0)
+    ocfg, zcfg = oracle_cfg(w, **kw), zi_cfg(w, **kw)
+    sumsq, flag = oracle.grad_sumsq([h[3] for h in host], dt)
+    exp = []
+    for (p, m, v, g) in host:
+        pe, me, ve, lpe = p.copy(), m.copy(), v.copy(), np.zeros(p.size, np.uint16)
+        oracle.adamw(pe, me, ve, g, lpe, dt, ocfg, sumsq, flag)
+        exp.append((pe, me, ve, lpe))
+    d_g = [to_dev(h[3]) for h in host]
+    nb = NormBuffers()
+    tl_norm = [(None, None, None, g, None, g.numel()) for g in d_g]
+    zi.zi_grad_norm(tl_norm, dt, kw["loss_scale"], nb.out, nb.ws)
+
+    def host_state():
+        if pinned:
+            return [tuple(_pinned(a) for a in h[:3]) for h in host]
+        return [tuple(torch.from_numpy(a.copy()) for a in h[:3]) for h in host]
+
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 4)
+        # reference: the GPU-side streamed step
+        st_a = host_state()
+        lp_a = [torch.zeros(n, dtype=torch.int16, device="cuda:0") for n in sizes]
+        assert zi.zi_adamw_step_streamed(eng, [(a[0], a[1], a[2], g, lp, n) for a, g, lp, n in
+                                               zip(st_a, d_g, lp_a, sizes)], dt, zcfg, nb.out) == zi.ZI_OK
+        # the CPU placement
+        st_b = host_state()
+        lp_b = [torch.full((n,), 0x5555, dtype=torch.int16, device="cuda:0") for n in sizes]
+        assert zi.zi_adamw_step_cpu(eng, [(b[0], b[1], b[2], g, lp, n) for b, g, lp, n in
+                                          zip(st_b, d_g, lp_b, sizes)], dt, zcfg, nb.out, 4,
+                                    torch.cuda.current_stream()) == zi.ZI_OK
+        stats = zi.zi_engine_last_stats(eng)
+        total = sum(sizes)
+        assert stats.bytes_d2h == 2 * total == stats.bytes_h2d
+        for i, n in enumerate(sizes):
+            for x, y in zip(st_a[i], st_b[i]):
+                assert np.array_equal(x.numpy().view(np.uint32), y.numpy().view(np.uint32)), f"tensor {i}"
+            assert torch.equal(lp_a[i], lp_b[i]), f"tensor {i}: copy"
+            got = (st_b[i][0].numpy(), st_b[i][1].numpy(), st_b[i][2].numpy(), to_np(lp_b[i]))
+            compare_state(exp[i], got, dt, f"cpu step tensor {i} ")
+        # overflow: nothing moves, nothing changes
+        bad = d_g[0].clone()
+        bad[11] = np.array([0x7F80 if dt == zi.ZI_BF16 else 0x7C00], np.uint16).view(np.int16)[0]
+        zi.zi_grad_norm([(None, None, None, bad, None, bad.numel())], dt, kw["loss_scale"], nb.out, nb.ws)
+        before = [x.clone() for x in st_b[0]]
+        lp_before = lp_b[0].clone()
+        assert zi.zi_adamw_step_cpu(eng, [(st_b[0][0], st_b[0][1], st_b[0][2], bad, lp_b[0], sizes[0])], dt, zcfg,
+                                    nb.out, 2) == zi.ZI_SKIPPED_OVERFLOW
+        assert all(torch.equal(x, y) for x, y in zip(before, st_b[0])) and torch.equal(lp_before, lp_b[0])
+        assert zi.zi_engine_last_stats(eng).bytes_d2h == 0
+        # everything in host memory: no ring needed, no link traffic
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 0)
+        st_c = host_state()
+        hg = [torch.from_numpy(h[3].view(np.int16).copy()) for h in host]
+        hlp = [torch.zeros(n, dtype=torch.int16) for n in sizes]
+        assert zi.zi_adamw_step_cpu(eng, [(c[0], c[1], c[2], g, lp, n) for c, g, lp, n in zip(st_c, hg, hlp, sizes)],
+                                    dt, zcfg, None, 3) == zi.ZI_OK
+        # (no norm result here: compare with the oracle without clipping)
+        for i, (p, m, v, g) in enumerate(host):
+            pe, me, ve, lpe = p.copy(), m.copy(), v.copy(), np.zeros(p.size, np.uint16)
+            oracle.adamw(pe, me, ve, g, lpe, dt, ocfg, None, 0)
+            compare_state((pe, me, ve, lpe), (st_c[i][0].numpy(), st_c[i][1].numpy(), st_c[i][2].numpy(),
+                                              hlp[i].numpy().view(np.uint16)), dt, f"cpu step, all host, tensor {i} ")
+        assert zi.zi_engine_last_stats(eng).bytes_d2h == 0 == zi.zi_engine_last_stats(eng).bytes_h2d
+        # device gradients without a ring are refused
+        with pytest.raises(zi.ZiError):
+            zi.zi_adamw_step_cpu(eng, [(st_c[0][0], st_c[0][1], st_c[0][2], d_g[0], None, sizes[0])], dt, zcfg, None, 2)
+    finally:
+        zi.zi_engine_destroy(eng)
+    progress(f"cpu step (dt={dt}, pinned={pinned}): equal to the streamed GPU step and to the oracle")

@@ -271,7 +271,7 @@ def _c2_streamed_from_pinned_host(n):
         nbytes = 1 << 30
         scratch = PinnedF32(nbytes // 4)
         try:
-            one_way = min(nbytes / zi.zi_engine_link_probe(eng, hp.ptr, scratch.ptr, nbytes, mode, 1)
+            one_way = min(nbytes / zi.zi_engine_link_probe(eng, hp.ptr, scratch.ptr, nbytes, mode)
                           for mode in (0, 1))
         finally:
             scratch.free()
