@@ -340,9 +340,12 @@ zi_status zi_engine_last_stats(const zi_engine* e, zi_stream_stats* out);
  * ZI_OPT_SKIP_KERNEL = 1 runs the identical copy pipeline without launching the
  * update (a measurement aid like the calls of zi_probe.h: the time of the pipeline with the update
  * removed).
- * ZI_OPT_MAX_INFLIGHT = k: before issuing a slot use the host waits for the use k positions back
- * to finish.  The default 2 keeps copy-in and copy-out in lockstep, which measured fastest and
- * steadiest; with n_slots = 3 the third slot then only decouples the host's issue from completion.
+ * ZI_OPT_MAX_INFLIGHT selects how the host paces the pipeline.  0 (default, needs n_slots >= 3): a slot
+ * use is issued when the copy-out of the use two positions back starts (its update is done);
+ * the two directions of the link then run side by side one chunk apart and the update of the chunk
+ * in between is hidden.  k >= 1: before issuing a slot use the host waits for the use k positions
+ * back to FINISH (k = 2 also keeps the directions in lockstep but exposes the update once per chunk;
+ * k = n_slots lets the copy-in stream run a whole slot ahead, which measured slower and unsteady).
  * ZI_OPT_HOST_RING_SLOTS = n gives the engine a ring of n pinned host slots
  * (each shaped like an HBM slot: 4 arrays of the chunk size) and two small CPU thread pools.  With it,
  * zi_adamw_step_streamed also accepts p, m, v in ORDINARY (pageable) host
@@ -356,7 +359,7 @@ typedef enum {
     ZI_OPT_SKIP_KERNEL = 0,
     ZI_OPT_HOST_RING_SLOTS = 1,    /* 0 = none (default); 2..16: allocate a pinned ring of that many slots */
     ZI_OPT_HOST_COPY_THREADS = 2,  /* 1..64 CPU threads per direction for the ring (default 6) */
-    ZI_OPT_MAX_INFLIGHT = 3        /* 1..n_slots slot uses the host keeps in flight (default 2) */
+    ZI_OPT_MAX_INFLIGHT = 3        /* 0 (default pacing) or 1..n_slots */
 } zi_engine_option;
 zi_status zi_engine_set_option(zi_engine* e, int32_t option, int64_t value);
 

@@ -49,6 +49,7 @@ struct zi_engine {
     char* staging = nullptr;
     hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
     hipEvent_t ev_h2d[8] = {}, ev_k[8] = {}, ev_d2h[8] = {};
+    hipEvent_t ev_out_start[8] = {};   // the slot's device-to-host copies are about to start (its update is done)
     hipEvent_t ev_in = nullptr, ev_out = nullptr;
     zi_norm_result* h_norm = nullptr;  // pinned landing place of the norm result
 
@@ -83,7 +84,7 @@ struct zi_engine {
 
     // options and figures
     int64_t skip_kernel = 0;
-    int max_inflight = 2;              // slot uses the host keeps in flight (<= n_slots)
+    int max_inflight = 0;              // 0: paced by the start of the copy-out two uses back; k: by the end of use - k
     zi_stream_stats stats{};
 
     float* slot_array(int slot, int which) const

@@ -11,6 +11,9 @@
 
 #include "zi_internal.h"
 #include "zi_checks.h"
+#include "zi_plan.h"
+
+static_assert(zi::host::kPlanMaxSegmentsPerUse == zi::kMaxStepDesc, "a packed slot use must fit one fused-step launch");
 
 namespace zi {
 namespace host {
@@ -296,18 +299,6 @@ struct NormIssuer {
     }
 };
 
-
-// Chunk plan of the streamed step (zi_plan.hip).
-constexpr int64_t kPackAlign = 1024; // packed segments start on 4096-byte boundaries of the slot arrays (direct file I/O)
-constexpr int64_t kPhasePad = 8;     // room for lead-in elements that keep alignment phases equal
-
-struct Segment {
-    int32_t tensor;
-    int64_t elem_offset, count, slot_use, slot_offset;
-};
-
-void plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems, std::vector<Segment>& out,
-                 int64_t& n_uses);
 
 }  // namespace host
 }  // namespace zi

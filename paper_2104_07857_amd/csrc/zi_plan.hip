@@ -3,45 +3,6 @@
 
 #include "zi_host.h"
 
-namespace zi {
-namespace host {
-
-// Pass 1: every whole chunk of every tensor takes a slot use of its own, in list order.
-// Pass 2: what is left (tensors shorter than a chunk and the remainders of long ones) is packed
-// first-fit, in list order, into shared slot uses of at most kMaxStepDesc segments each, so a
-// list with many tiny tensors between giant ones costs one extra slot use, not one per tensor.
-void plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems, std::vector<Segment>& out,
-                 int64_t& n_uses)
-{
-    out.clear();
-    int64_t use = 0;
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        const int64_t whole = numel[i] / chunk_elems;
-        for (int64_t c = 0; c < whole; ++c) out.push_back({i, c * chunk_elems, chunk_elems, use++, 0});
-    }
-    int64_t fill = 0;          // next free element of the open packed slot use
-    int packed = 0;            // segments in the open packed slot use
-    bool open = false;
-    for (int32_t i = 0; i < n_tensors; ++i) {
-        const int64_t off = numel[i] / chunk_elems * chunk_elems;
-        const int64_t left = numel[i] - off;
-        if (left == 0) continue;
-        if (open && (fill + left + kPhasePad > chunk_elems || packed == zi::kMaxStepDesc)) {
-            ++use;
-            open = false;
-        }
-        if (!open) { open = true; fill = 0; packed = 0; }
-        out.push_back({i, off, left, use, fill});
-        ++packed;
-        fill = (fill + left + kPhasePad + kPackAlign - 1) / kPackAlign * kPackAlign;
-    }
-    if (open) ++use;
-    n_uses = use;
-}
-
-}  // namespace host
-}  // namespace zi
-
 using namespace zi::host;
 
 extern "C" zi_status zi_plan_chunks(const int64_t* numel, int32_t n_tensors, int64_t chunk_elems,
