@@ -103,3 +103,49 @@ def test_more_blocks_than_the_array_holds_and_the_list_limit():
     torch.cuda.synchronize()
     want, _ = oracle.grad_sumsq([big[:zi.ZI_NOALLOC_MAX_PARTIALS].cpu().numpy().view(np.uint16)], dt)
     assert abs(_read(out)[0] - want) <= 1e-12 * want
+
+
+def test_captured_into_a_graph_with_the_step():
+    """What the entry point is for: under stream capture nothing may allocate.  zi_grad_norm_noalloc and
+    zi_adamw_step are captured once (after one eager call has looked up the array's address) and replayed
+    three times with eager work in between; every replay equals the same number of eager steps."""
+    from gpu_util import gen_numpy, zi_cfg
+    w = zi_synth.workload("c4")
+    dt = zi.ZI_BF16
+    rng = np.random.default_rng(3)
+    numel = [int(x) for x in rng.integers(1, 60_000, 40)] + [1_000_003]
+    spec = zi_synth.StateSpec(77, dt, g_std=2e-3)
+    host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(numel)]
+
+    def device_copy():
+        ts = [tuple(to_dev(a) for a in t) + (torch.zeros(t[0].size, dtype=torch.int16, device="cuda:0"),) for t in host]
+        return ts, zi.make_tensors([t + (t[0].numel(),) for t in ts])
+
+    cfg = zi_cfg(w)
+    eager, eager_tl = device_copy()
+    graphed, graphed_tl = device_copy()
+    out_e = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    out_g = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    zi.zi_grad_norm_noalloc(eager_tl, dt, 1.0, out_e)            # first call on this device: not under capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        zi.zi_grad_norm_noalloc(graphed_tl, dt, 1.0, out_g, stream=side)
+        zi.zi_adamw_step(graphed_tl, dt, cfg, out_g, stream=side)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for a, b in zip(eager, graphed):
+        assert torch.equal(a[0], b[0])                           # capture executed nothing
+    for replay in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        zi.zi_grad_norm_noalloc(eager_tl, dt, 1.0, out_e)
+        zi.zi_adamw_step(eager_tl, dt, cfg, out_e)
+        torch.cuda.synchronize()
+        assert torch.rand(1 << 18, device="cuda:0").sum().item() > 0          # unrelated eager work between replays
+        assert _read(out_e) == _read(out_g), f"replay {replay}: norm result differs"
+        for i, (a, b) in enumerate(zip(eager, graphed)):
+            for x, y in zip(a, b):
+                assert torch.equal(x, y), f"replay {replay}, tensor {i}"
