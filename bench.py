@@ -48,6 +48,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="leave out the oracle (timing and parity)")
     ap.add_argument("--no-streamed", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="headline workload only (profiling runs)")
+    ap.add_argument("--extras", default="c0,c3,c4,streamed", help="comma-separated extras to run (profiling runs)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (scales rocprofv3 byte counters)")
     ap.add_argument("--file-numel", type=int, default=1 << 28,
@@ -749,11 +750,14 @@ def main():
                 extras[name] = dict(error=f"{type(e).__name__}: {e}")
                 log(f"{name} failed: {e}")
             torch.cuda.empty_cache()
-        if not args.no_cpu_baseline:
+        want = set(args.extras.split(","))
+        if not args.no_cpu_baseline and "c0" in want:
             attempt("c0", extra_c0)
+        if not args.no_cpu_baseline and "c3" in want:
             attempt("c3", extra_c3)
-        attempt("c4", extra_c4)
-        if not args.no_streamed:
+        if "c4" in want:
+            attempt("c4", extra_c4)
+        if not args.no_streamed and "streamed" in want:
             attempt("streamed", streamed)
     line = {
         "metric": "AdamW step params/s + % HBM peak (resident); % host-link BW (streamed)",
