@@ -135,6 +135,20 @@ def test_engine_and_misc_argument_checks():
         zi.zi_engine_file_probe(None, -1, -1, 4096)
     with pytest.raises(zi.ZiError):
         zi.zi_engine_last_stats(None)
+    # the calls added around the streamed step refuse a missing engine the same way, before anything else
+    for call in (lambda: zi.zi_grad_offload(None, p, m, 64),
+                 lambda: zi.zi_grad_offload_wait(None),
+                 lambda: zi.zi_grad_offload_order(None),
+                 lambda: zi.zi_adamw_step_cpu(None, [(p, m, v, g, lp)], zi.ZI_BF16, zi.make_config(), None, 2),
+                 lambda: zi.zi_engine_link_probe(None, p, m, 64, 0),
+                 lambda: zi.zi_grad_norm_streamed(None, [(None, None, None, g, None, 64)], zi.ZI_BF16, 1.0, 8, 16, 1 << 20)):
+        with pytest.raises(zi.ZiError) as e:
+            call()
+        assert e.value.status == zi.ZI_ERR_INVALID_ARG and "engine" in e.value.message
+    # the no-allocation reduction validates like zi_grad_norm (no GPU here: the device query fails first)
+    with pytest.raises(zi.ZiError) as e:
+        zi.zi_grad_norm_noalloc([(None, None, None, g, None, 64)], zi.ZI_BF16, 1.0, 8)
+    assert e.value.status in (zi.ZI_ERR_HIP, zi.ZI_ERR_INVALID_ARG)
     with pytest.raises(zi.ZiError):
         zi.zi_engine_set_option(None, 0, 1)
     buf = np.zeros(64, np.float32)
