@@ -114,7 +114,10 @@ inline int choose_head(const void* p, const void* m, const void* v, const void* 
 
 // Tensors of at least this many tiles (2^22 elements, some 20 microseconds of HBM time) are launched
 // alone; shorter ones share launches of up to kMaxStepDesc tensors.
-constexpr int64_t kSoloTiles = 8192;
+#ifndef ZI_SOLO_TILES
+#define ZI_SOLO_TILES 8192
+#endif
+constexpr int64_t kSoloTiles = ZI_SOLO_TILES;
 
 // Issues the fused step over a list of device-resident segments.
 struct StepIssuer {
