@@ -655,3 +655,61 @@ def test_cpu_step_with_device_gradients_and_copy(dt, pinned):
     finally:
         zi.zi_engine_destroy(eng)
     progress(f"cpu step (dt={dt}, pinned={pinned}): equal to the streamed GPU step and to the oracle")
+
+
+def test_many_small_offloads_reuse_the_event_ring_and_order_a_consumer_stream():
+    """More offloads than the engine has events (the ring of 64 is reused), each behind its own producer
+    write; a consumer stream ordered with zi_grad_offload_order then reads the host copy through a
+    host-to-device copy without any host-side wait."""
+    k, part = 150, 4096
+    dev = "cuda:0"
+    gbuf = torch.zeros(k * part, dtype=torch.int32, device=dev)
+    host = torch.zeros(k * part, dtype=torch.int32, pin_memory=True)
+    back = torch.zeros(k * part, dtype=torch.int32, device=dev)
+    producer, consumer = torch.cuda.Stream(), torch.cuda.Stream()
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        for i in range(k):
+            with torch.cuda.stream(producer):
+                gbuf[i * part:(i + 1) * part] = i + 1
+            zi.zi_grad_offload(eng, gbuf[i * part:], host[i * part:], 4 * part, producer)
+        zi.zi_grad_offload_order(eng, consumer)
+        with torch.cuda.stream(consumer):
+            back.copy_(host, non_blocking=True)
+        consumer.synchronize()
+        want = torch.arange(1, k + 1, dtype=torch.int32, device=dev).repeat_interleave(part)
+        assert torch.equal(back, want)
+        assert zi.zi_grad_offload_wait(eng) == zi.ZI_OK and zi.zi_grad_offload_wait(eng) == zi.ZI_OK
+        assert torch.equal(host.to(dev), want)
+    finally:
+        zi.zi_engine_destroy(eng)
+
+
+def test_cpu_step_over_a_long_ragged_list():
+    """More short tensors than one slot use packs (32 segments), zero-length entries and tensors without a
+    copy: zi_adamw_step_cpu against the oracle."""
+    dt = zi.ZI_BF16
+    w = zi_synth.workload("c4")
+    rng = np.random.default_rng(8)
+    sizes = [int(x) for x in rng.integers(0, 3000, 90)] + [16384 * 2 + 9, 0, 5]
+    spec = zi_synth.StateSpec(99, dt)
+    host = [gen_numpy(spec, n, tensor=i) for i, n in enumerate(sizes)]
+    ocfg, zcfg = oracle_cfg(w, max_grad_norm=0.0), zi_cfg(w, max_grad_norm=0.0)
+    st = [tuple(torch.from_numpy(a.copy()) for a in h[:3]) for h in host]
+    d_g = [to_dev(h[3]) for h in host]
+    lps = [None if i % 7 == 3 else torch.zeros(n, dtype=torch.int16, device="cuda:0") for i, n in enumerate(sizes)]
+    eng = zi.zi_engine_create(0, 64 * 1024, 3)
+    try:
+        zi.zi_engine_set_option(eng, zi.ZI_OPT_HOST_RING_SLOTS, 3)
+        assert zi.zi_adamw_step_cpu(eng, [(s[0], s[1], s[2], g, lp, n) for s, g, lp, n in zip(st, d_g, lps, sizes)],
+                                    dt, zcfg, None, 3) == zi.ZI_OK
+        stats = zi.zi_engine_last_stats(eng)
+        assert stats.bytes_d2h == 2 * sum(sizes)
+        assert stats.bytes_h2d == 2 * sum(n for n, lp in zip(sizes, lps) if lp is not None)
+    finally:
+        zi.zi_engine_destroy(eng)
+    for i, (p, m, v, g) in enumerate(host):
+        lpe = np.zeros(p.size, np.uint16)
+        oracle.adamw(p, m, v, g, lpe, dt, ocfg, None, 0)
+        got = (st[i][0].numpy(), st[i][1].numpy(), st[i][2].numpy(), None if lps[i] is None else to_np(lps[i]))
+        compare_state((p, m, v, None if lps[i] is None else lpe), got, dt, f"tensor {i} ")
