@@ -86,12 +86,21 @@ __device__ __forceinline__ void adamw_element(float& p, float& m, float& v, floa
 // here from the sum of squares and the step's own loss scale (not read from the result's `norm`
 // field), so the scale given to the reduction cannot disagree with the one the step unscales by.
 // Returns false if the step must be skipped.
+//
+// The result is read through the constant address space, which makes the three reads scalar loads:
+// they are served by the scalar cache in a few hundred cycles.  As ordinary global loads they would
+// join the vector memory pipeline behind the streaming traffic of the other wavefronts, and every
+// wavefront would spend a full loaded-memory round trip (as long as its real loads take) before it
+// issues anything, which costs 4 points of bandwidth.  The result was written by an earlier kernel
+// on the stream and nothing writes it while the step runs, which is what that address space asks.
+typedef const __attribute__((address_space(4))) zi_norm_result* NormResultK;
 __device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, const StepConsts& c, float& gscale)
 {
     gscale = c.host_gscale;
     if (d_norm) {
-        if (d_norm->found_inf) return false;
-        const double norm = __builtin_sqrt(d_norm->sumsq) / (double)c.loss_scale;
+        const NormResultK r = (NormResultK)(uintptr_t)d_norm;
+        if (r->found_inf) return false;
+        const double norm = __builtin_sqrt(r->sumsq) / (double)c.loss_scale;
         const double mx = (double)c.max_grad_norm;
         double clip = 1.0;
         if (c.max_grad_norm > 0.0f && norm + 1e-6 > mx) clip = mx / (norm + 1e-6);
