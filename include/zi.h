@@ -110,7 +110,7 @@ typedef struct {
     double sumsq;          /* sum of squares of the raw (still loss-scaled) gradients */
     double norm;           /* sqrt(sumsq) / loss_scale; meaningful only if found_inf == 0 */
     uint32_t found_inf;    /* 1 if any gradient element is +-inf or NaN, else 0 */
-    uint32_t reserved;
+    uint32_t scale_bits;   /* bit pattern of the (float) loss scale `norm` was divided by; written by the library */
 } zi_norm_result;
 
 /* One tensor of the owned partition.  All arrays hold numel elements. */
@@ -191,10 +191,13 @@ zi_status zi_norm_refresh(zi_norm_result* d_result, float loss_scale, void* hip_
  * d_norm: device result of zi_grad_norm on the same gradients, or NULL.  With
  * NULL there is no overflow check and no clipping: gscale = 1 / loss_scale.
  * With a result, the kernels read it on the device: found_inf != 0 skips the
- * whole step, otherwise the clip factor is derived from d_norm->sumsq and
- * cfg->loss_scale (norm = sqrt(sumsq) / cfg->loss_scale; the result's own
- * `norm` field is informational and is not read, so the scale that was given
- * to zi_grad_norm does not matter here).
+ * whole step, otherwise the clip factor follows from norm = sqrt(sumsq) /
+ * cfg->loss_scale.  The result's own `norm` field is taken for that value only
+ * when its `scale_bits` field says it was divided by cfg->loss_scale (the
+ * library writes the two together); a result reduced with any other scale
+ * has its norm derived again from `sumsq`, so the scale that was given to
+ * zi_grad_norm cannot make the step clip wrongly.  A caller that edits
+ * `sumsq` in place (a sharded run) calls zi_norm_refresh afterwards.
  * Asynchronous on hip_stream; the return value is ZI_OK even when the device
  * will skip the step (read d_norm->found_inf to learn of it).
  */

@@ -15,7 +15,9 @@ struct StepConsts {
     float beta1, beta2, omb1, omb2, eps, step_size, inv_sqrt_bc2, decay, weight_decay;
     float loss_scale;      // as given by the caller
     float max_grad_norm;   // <= 0: no clipping
-    float host_gscale;     // 1 / loss_scale, used when no norm result is given
+    float host_gscale;     // 1 / loss_scale: the gradient factor of a step that does not clip
+    uint32_t scale_is_pow2;     // loss_scale is a power of two: dividing by it is multiplying by its inverse, exactly
+    double inv_loss_scale;      // 1 / loss_scale in double (exact when scale_is_pow2)
 };
 
 namespace host {
@@ -96,6 +98,9 @@ inline zi::StepConsts make_consts(const zi_adamw_config& c)
     k.loss_scale = c.loss_scale;
     k.max_grad_norm = c.max_grad_norm;
     k.host_gscale = (float)(1.0 / (double)c.loss_scale);
+    int exponent = 0;
+    k.scale_is_pow2 = std::frexp((double)c.loss_scale, &exponent) == 0.5 ? 1u : 0u;
+    k.inv_loss_scale = 1.0 / (double)c.loss_scale;
     return k;
 }
 

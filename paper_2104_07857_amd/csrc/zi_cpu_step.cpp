@@ -259,7 +259,9 @@ extern "C" zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi
         h_out->sumsq = sum;
         h_out->norm = std::sqrt(sum) / (double)loss_scale;
         h_out->found_inf = found ? 1u : 0u;
-        h_out->reserved = 0;
+        uint32_t bits;
+        std::memcpy(&bits, &loss_scale, sizeof bits);
+        h_out->scale_bits = bits;
         return ZI_OK;
     } catch (const std::exception& ex) {
         return fail(ZI_ERR_NOMEM, "host step: %s", ex.what());

@@ -82,17 +82,26 @@ __device__ __forceinline__ void adamw_element(float& p, float& m, float& v, floa
     v = v1;
 }
 
-// Skip decision and gradient factor, from the device-resident norm result.  The norm is derived
-// here from the sum of squares and the step's own loss scale (not read from the result's `norm`
-// field), so the scale given to the reduction cannot disagree with the one the step unscales by.
-// Returns false if the step must be skipped.
+// Skip decision and gradient factor, from the device-resident norm result: norm = sqrt(sumsq) /
+// loss_scale, clip = max_norm / (norm + 1e-6) where that is below 1, factor = clip / loss_scale, in
+// double, rounded once to fp32.  Returns false if the step must be skipped.
 //
-// The result is read through the constant address space, which makes the three reads scalar loads:
-// they are served by the scalar cache in a few hundred cycles.  As ordinary global loads they would
+// Every wavefront runs this before it issues its first load and lives for a few microseconds, so
+// the dependent chain is kept short (an fp64 square root and three divisions cost 5 points of
+// bandwidth on some devices); each shortcut gives the same bits as the full expression:
+//   - a step that does not clip uses the factor the host prepared, (float)(1 / loss_scale);
+//   - the result's `norm` is used when its `scale_bits` say it was divided by this step's loss scale
+//     (the reduction wrote both); with any other scale the norm is derived from the sum of squares,
+//     so a reduction called with a different scale cannot make the step clip wrongly;
+//   - dividing by a loss scale that is a power of two is multiplying by its inverse, which is exact.
+// What is left in the usual case is one fp64 division.
+//
+// The result is read through the constant address space, which makes the reads scalar loads: they
+// are served by the scalar cache in a few hundred cycles.  As ordinary global loads they would
 // join the vector memory pipeline behind the streaming traffic of the other wavefronts, and every
 // wavefront would spend a full loaded-memory round trip (as long as its real loads take) before it
-// issues anything, which costs 4 points of bandwidth.  The result was written by an earlier kernel
-// on the stream and nothing writes it while the step runs, which is what that address space asks.
+// issues anything, which costs 4 to 9 points of bandwidth.  The result was written by an earlier
+// kernel on the stream and nothing writes it while the step runs, which is what that address space asks.
 typedef const __attribute__((address_space(4))) zi_norm_result* NormResultK;
 __device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, const StepConsts& c, float& gscale)
 {
@@ -100,11 +109,15 @@ __device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, cons
     if (d_norm) {
         const NormResultK r = (NormResultK)(uintptr_t)d_norm;
         if (r->found_inf) return false;
-        const double norm = __builtin_sqrt(r->sumsq) / (double)c.loss_scale;
-        const double mx = (double)c.max_grad_norm;
-        double clip = 1.0;
-        if (c.max_grad_norm > 0.0f && norm + 1e-6 > mx) clip = mx / (norm + 1e-6);
-        gscale = (float)(clip / (double)c.loss_scale);
+        if (c.max_grad_norm > 0.0f) {
+            const double ls = (double)c.loss_scale;
+            const double norm = r->scale_bits == __float_as_uint(c.loss_scale) ? r->norm : __builtin_sqrt(r->sumsq) / ls;
+            const double mx = (double)c.max_grad_norm;
+            if (norm + 1e-6 > mx) {
+                const double clip = mx / (norm + 1e-6);
+                gscale = (float)(c.scale_is_pow2 ? clip * c.inv_loss_scale : clip / ls);
+            }
+        }
     }
     return true;
 }
@@ -488,7 +501,7 @@ __global__ __launch_bounds__(kFinalThreads) void norm_finalize_kernel(const Norm
         r.sumsq = sum;
         r.norm = __builtin_sqrt(sum) / (double)loss_scale;
         r.found_inf = flag ? 1u : 0u;
-        r.reserved = 0;
+        r.scale_bits = __float_as_uint(loss_scale);
         *out = r;
     }
 }
@@ -500,6 +513,7 @@ __global__ void norm_refresh_kernel(zi_norm_result* r, float loss_scale)
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         r->norm = __builtin_sqrt(r->sumsq) / (double)loss_scale;
         r->found_inf = r->found_inf ? 1u : 0u;
+        r->scale_bits = __float_as_uint(loss_scale);
     }
 }
 

@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 TILE = 512    # elements one workgroup covers
 
 
-def _run_both(p, m, v, g, dt, ocfg, zcfg, with_lp=True, use_norm=False, offsets=None):
-    """Steps numpy state through the oracle and through zi_adamw_step; returns (expected, got, info)."""
+def _run_both(p, m, v, g, dt, ocfg, zcfg, with_lp=True, use_norm=False, offsets=None, norm_scale=None):
+    """Steps numpy state through the oracle and through zi_adamw_step; returns (expected, got, info).
+    norm_scale: loss scale handed to zi_grad_norm when it is to differ from the step's own."""
     n = p.size
     pe, me, ve = p.copy(), m.copy(), v.copy()
     lpe = np.zeros(n, np.uint16) if with_lp else None
@@ -36,7 +37,7 @@ def _run_both(p, m, v, g, dt, ocfg, zcfg, with_lp=True, use_norm=False, offsets=
     nb = None
     if use_norm:
         nb = NormBuffers()
-        zi.zi_grad_norm([(None, None, None, dg, None, n)], dt, ocfg.loss_scale, nb.out, nb.ws)
+        zi.zi_grad_norm([(None, None, None, dg, None, n)], dt, norm_scale or ocfg.loss_scale, nb.out, nb.ws)
     st = zi.zi_adamw_step([(dp, dm, dv, dg, dlp if with_lp else None, n)], dt, zcfg,
                           None if nb is None else nb.out)
     assert st == zi.ZI_OK
@@ -167,6 +168,27 @@ def test_loss_scale_clip_and_overflow_skip_small():
     for a, b in zip((p, m, v), got[:3]):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
     assert not got[3].any()
+
+
+@pytest.mark.parametrize("step_scale,norm_scale", [(65536.0, 65536.0), (65536.0, 1.0), (65536.0, 1024.0),
+                                                   (1000.0, 1000.0), (1000.0, 65536.0), (3.0, 0.75)])
+def test_clip_follows_the_steps_own_loss_scale_whatever_scale_the_reduction_was_given(step_scale, norm_scale):
+    """The step takes the reduction's norm only when it was divided by the step's own loss scale and derives it
+    from the sum of squares otherwise; a power-of-two scale is applied by an exact multiplication, any other by
+    a division.  Every combination has to give the oracle's bits."""
+    w = zi_synth.workload("c3")
+    n = 70_001
+    dt = zi.ZI_FP16
+    spec = zi_synth.StateSpec(777, dt, g_std=w["spec"].g_std * step_scale / 65536.0)
+    p, m, v, g = gen_numpy(spec, n)
+    over = dict(loss_scale=step_scale, max_grad_norm=0.05)
+    exp, got, info = _run_both(p, m, v, g, dt, oracle_cfg(w, **over), zi_cfg(w, **over), use_norm=True,
+                               norm_scale=norm_scale)
+    assert info["flag"] == 0 and info["norm"][2] == 0
+    assert oracle.scalars(oracle_cfg(w, **over), info["sumsq"]).clip < 0.5      # the clip is active
+    want_norm = float(np.sqrt(info["sumsq"]) / norm_scale)
+    assert abs(info["norm"][1] - want_norm) <= 1e-6 * want_norm                 # the reduction used its own scale
+    progress(f"clip with step scale {step_scale}, reduction scale {norm_scale}: " + compare_state(exp, got, dt, ""))
 
 
 def test_power_of_two_loss_scale_is_invisible_on_the_device():
