@@ -194,7 +194,7 @@ def resident(args, torch, zi, zs):
                          weight_decay=w["weight_decay"], step=w["step"], loss_scale=w["loss_scale"],
                          max_grad_norm=w["max_grad_norm"])
     tl = zi.make_tensors([(p, m, v, g, lp, n)])
-    d_norm = torch.zeros(3, dtype=torch.float64, device=dev)
+    d_norm = torch.zeros(4, dtype=torch.float64, device=dev)
     ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
@@ -279,7 +279,7 @@ def extra_c0(args, torch, zi, zs):
     cfg = zi.make_config(lr=w["lr"], beta1=w["beta1"], beta2=w["beta2"], eps=w["eps"],
                          weight_decay=w["weight_decay"], step=w["step"])
     tl = zi.make_tensors([(p, m, v, g, lp, n)])
-    d_norm = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    d_norm = torch.zeros(4, dtype=torch.float64, device="cuda:0")
     ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
     stream = torch.cuda.current_stream()
     zi.zi_grad_norm(tl, dt, 1.0, d_norm, ws, stream=stream)
@@ -310,7 +310,7 @@ def extra_c3(args, torch, zi, zs):
                          weight_decay=w["weight_decay"], step=w["step"], loss_scale=w["loss_scale"],
                          max_grad_norm=w["max_grad_norm"])
     tl = zi.make_tensors([(p, m, v, g, lp, n)])
-    d_norm = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    d_norm = torch.zeros(4, dtype=torch.float64, device="cuda:0")
     ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
     stream = torch.cuda.current_stream()
     # run A
@@ -403,7 +403,7 @@ def extra_c4(args, torch, zi, zs):
             spec.fill_g(st16, n, i)
             grads.append(torch.from_numpy(st16[:n]).to("cuda:0"))
             lps.append(torch.zeros(n, dtype=torch.int16, device="cuda:0"))
-        d_norm = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+        d_norm = torch.zeros(4, dtype=torch.float64, device="cuda:0")
         ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
         stream = torch.cuda.current_stream()
         tl_s = zi.make_tensors([(ptrs[1 + 3 * i], ptrs[2 + 3 * i], ptrs[3 + 3 * i], grads[i], lps[i], n)
@@ -559,7 +559,7 @@ def streamed(args, torch, zi, zs):
         log("streamed: gradients and copy offloaded too")
         hg = zi.zi_pinned_alloc(2 * ns)
         hlp = zi.zi_pinned_alloc(2 * ns)
-        d_norm = torch.zeros(3, dtype=torch.float64, device=dev)
+        d_norm = torch.zeros(4, dtype=torch.float64, device=dev)
         ws = torch.empty(zi.zi_norm_workspace_bytes(), dtype=torch.uint8, device=dev)
         producer = torch.cuda.Stream()
         part = 1 << 26                                          # 64 Mi elements = 128 MiB per partition

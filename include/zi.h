@@ -105,12 +105,15 @@ typedef struct {
     int32_t mode;          /* zi_mode */
 } zi_adamw_config;
 
-/* Result of zi_grad_norm.  Lives in DEVICE memory, 8-byte aligned, 24 bytes. */
+/* Result of zi_grad_norm.  Lives in DEVICE memory, 8-byte aligned, 32 bytes.  The last two
+ * fields are derived values the library writes together with `norm` so that the step's kernels
+ * need not recompute them in every wavefront; a caller never sets them. */
 typedef struct {
     double sumsq;          /* sum of squares of the raw (still loss-scaled) gradients */
     double norm;           /* sqrt(sumsq) / loss_scale; meaningful only if found_inf == 0 */
     uint32_t found_inf;    /* 1 if any gradient element is +-inf or NaN, else 0 */
-    uint32_t scale_bits;   /* bit pattern of the (float) loss scale `norm` was divided by; written by the library */
+    uint32_t scale_bits;   /* bit pattern of the (float) loss scale `norm` was divided by */
+    double inv_norm;       /* 1 / (norm + 1e-6): the clip factor for a maximum norm of 1 */
 } zi_norm_result;
 
 /* One tensor of the owned partition.  All arrays hold numel elements. */
@@ -197,7 +200,8 @@ zi_status zi_norm_refresh(zi_norm_result* d_result, float loss_scale, void* hip_
  * library writes the two together); a result reduced with any other scale
  * has its norm derived again from `sumsq`, so the scale that was given to
  * zi_grad_norm cannot make the step clip wrongly.  A caller that edits
- * `sumsq` in place (a sharded run) calls zi_norm_refresh afterwards.
+ * `sumsq` in place (a sharded run) calls zi_norm_refresh afterwards, which
+ * rewrites `norm`, `scale_bits` and `inv_norm`.
  * Asynchronous on hip_stream; the return value is ZI_OK even when the device
  * will skip the step (read d_norm->found_inf to learn of it).
  */

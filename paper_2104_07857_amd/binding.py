@@ -54,7 +54,7 @@ class zi_adamw_config(ctypes.Structure):
 
 class zi_norm_result(ctypes.Structure):
     _fields_ = [("sumsq", ctypes.c_double), ("norm", ctypes.c_double), ("found_inf", ctypes.c_uint32),
-                ("scale_bits", ctypes.c_uint32)]
+                ("scale_bits", ctypes.c_uint32), ("inv_norm", ctypes.c_double)]
 
 
 class zi_tensor(ctypes.Structure):

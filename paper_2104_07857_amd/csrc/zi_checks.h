@@ -17,6 +17,7 @@ struct StepConsts {
     float max_grad_norm;   // <= 0: no clipping
     float host_gscale;     // 1 / loss_scale: the gradient factor of a step that does not clip
     uint32_t scale_is_pow2;     // loss_scale is a power of two: dividing by it is multiplying by its inverse, exactly
+    uint32_t max_norm_is_pow2;  // max_grad_norm is a power of two: max_grad_norm / x is max_grad_norm * (1 / x), exactly
     double inv_loss_scale;      // 1 / loss_scale in double (exact when scale_is_pow2)
 };
 
@@ -101,6 +102,7 @@ inline zi::StepConsts make_consts(const zi_adamw_config& c)
     int exponent = 0;
     k.scale_is_pow2 = std::frexp((double)c.loss_scale, &exponent) == 0.5 ? 1u : 0u;
     k.inv_loss_scale = 1.0 / (double)c.loss_scale;
+    k.max_norm_is_pow2 = c.max_grad_norm > 0.0f && std::frexp((double)c.max_grad_norm, &exponent) == 0.5 ? 1u : 0u;
     return k;
 }
 

@@ -262,6 +262,7 @@ extern "C" zi_status zi_host_grad_norm(const zi_tensor* t, int32_t n_tensors, zi
         uint32_t bits;
         std::memcpy(&bits, &loss_scale, sizeof bits);
         h_out->scale_bits = bits;
+        h_out->inv_norm = 1.0 / (h_out->norm + 1e-6);
         return ZI_OK;
     } catch (const std::exception& ex) {
         return fail(ZI_ERR_NOMEM, "host step: %s", ex.what());

@@ -93,8 +93,10 @@ __device__ __forceinline__ void adamw_element(float& p, float& m, float& v, floa
 //   - the result's `norm` is used when its `scale_bits` say it was divided by this step's loss scale
 //     (the reduction wrote both); with any other scale the norm is derived from the sum of squares,
 //     so a reduction called with a different scale cannot make the step clip wrongly;
-//   - dividing by a loss scale that is a power of two is multiplying by its inverse, which is exact.
-// What is left in the usual case is one fp64 division.
+//   - dividing by a loss scale that is a power of two is multiplying by its inverse, which is exact;
+//   - with a maximum norm that is a power of two (1 is the usual value) the quotient max_norm /
+//     (norm + 1e-6) is the reduction's 1 / (norm + 1e-6) times that power, again exactly.
+// What is left in the usual case is a comparison and two multiplications.
 //
 // The result is read through the constant address space, which makes the reads scalar loads: they
 // are served by the scalar cache in a few hundred cycles.  As ordinary global loads they would
@@ -102,19 +104,31 @@ __device__ __forceinline__ void adamw_element(float& p, float& m, float& v, floa
 // wavefront would spend a full loaded-memory round trip (as long as its real loads take) before it
 // issues anything, which costs 4 to 9 points of bandwidth.  The result was written by an earlier
 // kernel on the stream and nothing writes it while the step runs, which is what that address space asks.
-typedef const __attribute__((address_space(4))) zi_norm_result* NormResultK;
+// All 32 bytes are fetched by one load in front of the first branch: field-by-field reads would be
+// sunk into the branches that use them, one dependent round trip to the scalar cache each.
+typedef uint32_t u32x8_k __attribute__((ext_vector_type(8), aligned(8)));
+static_assert(sizeof(zi_norm_result) == 32, "the prologue reads the result as eight dwords");
+__device__ __forceinline__ double dwords_as_double(uint32_t lo, uint32_t hi)
+{
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, const StepConsts& c, float& gscale)
 {
     gscale = c.host_gscale;
     if (d_norm) {
-        const NormResultK r = (NormResultK)(uintptr_t)d_norm;
-        if (r->found_inf) return false;
+        const u32x8_k raw = *(const __attribute__((address_space(4))) u32x8_k*)(uintptr_t)d_norm;
+        const double sumsq = dwords_as_double(raw[0], raw[1]);
+        const double r_norm = dwords_as_double(raw[2], raw[3]);
+        const uint32_t found_inf = raw[4], scale_bits = raw[5];
+        const double r_inv_norm = dwords_as_double(raw[6], raw[7]);
+        if (found_inf) return false;
         if (c.max_grad_norm > 0.0f) {
             const double ls = (double)c.loss_scale;
-            const double norm = r->scale_bits == __float_as_uint(c.loss_scale) ? r->norm : __builtin_sqrt(r->sumsq) / ls;
+            const bool same_scale = scale_bits == __float_as_uint(c.loss_scale);
+            const double norm = same_scale ? r_norm : __builtin_sqrt(sumsq) / ls;
             const double mx = (double)c.max_grad_norm;
             if (norm + 1e-6 > mx) {
-                const double clip = mx / (norm + 1e-6);
+                const double clip = same_scale && c.max_norm_is_pow2 ? mx * r_inv_norm : mx / (norm + 1e-6);
                 gscale = (float)(c.scale_is_pow2 ? clip * c.inv_loss_scale : clip / ls);
             }
         }
@@ -169,9 +183,16 @@ __device__ __forceinline__ void store_stream(V* a, V x)
     *a = x;
 #endif
 }
-// The same for the element-aligned lane vectors (written out: an alignment attribute on a typedef
-// does not survive template argument deduction).
-__device__ __forceinline__ f32x4 load_stream_any(const f32x4_mem* a)
+// The same for the element-aligned lane vectors of the fused step (written out: an alignment attribute
+// on a typedef does not survive template argument deduction).  The pointers carry the global address
+// space in their type, so the accesses stay global_load / global_store wherever the pointer value
+// has been through (a pointer of unknown provenance would make them flat accesses, which also tie up
+// the scalar-memory counter and force the compiler to wait for all loads at once).
+#define ZI_GLOBAL __attribute__((address_space(1)))
+typedef ZI_GLOBAL f32x4_mem* GlobalF4;
+typedef ZI_GLOBAL u32x2_mem* GlobalU2;
+typedef const ZI_GLOBAL u32x2_mem* GlobalConstU2;
+__device__ __forceinline__ f32x4 load_stream_any(const ZI_GLOBAL f32x4_mem* a)
 {
 #if ZI_NT_LOAD
     return __builtin_nontemporal_load(a);
@@ -179,7 +200,7 @@ __device__ __forceinline__ f32x4 load_stream_any(const f32x4_mem* a)
     return *a;
 #endif
 }
-__device__ __forceinline__ u32x2 load_stream_any(const u32x2_mem* a)
+__device__ __forceinline__ u32x2 load_stream_any(const ZI_GLOBAL u32x2_mem* a)
 {
 #if ZI_NT_LOAD
     return __builtin_nontemporal_load(a);
@@ -187,7 +208,7 @@ __device__ __forceinline__ u32x2 load_stream_any(const u32x2_mem* a)
     return *a;
 #endif
 }
-__device__ __forceinline__ void store_stream_any(f32x4_mem* a, f32x4 x)
+__device__ __forceinline__ void store_stream_any(ZI_GLOBAL f32x4_mem* a, f32x4 x)
 {
 #if ZI_NT_STORE
     __builtin_nontemporal_store(x, a);
@@ -195,7 +216,7 @@ __device__ __forceinline__ void store_stream_any(f32x4_mem* a, f32x4 x)
     *a = x;
 #endif
 }
-__device__ __forceinline__ void store_stream_any(u32x2_mem* a, u32x2 x)
+__device__ __forceinline__ void store_stream_any(ZI_GLOBAL u32x2_mem* a, u32x2 x)
 {
 #if ZI_NT_STORE
     __builtin_nontemporal_store(x, a);
@@ -237,9 +258,6 @@ template <int DT, bool L2, bool SINGLE>
 __global__ __launch_bounds__(kStepThreads) __attribute__((amdgpu_waves_per_eu(1, 2)))
 void adamw_wide_kernel(const StepArgs a)
 {
-    float gscale;
-    if (!step_prologue(a.d_norm, a.c, gscale)) return;
-
     const uint32_t block = blockIdx.x;
     int d = 0;
     if constexpr (!SINGLE) {
@@ -271,6 +289,22 @@ void adamw_wide_kernel(const StepArgs a)
     }
     const int64_t tile = ti;
 
+    GlobalF4 __restrict__ p4 = (GlobalF4)(uintptr_t)(T.p + head);
+    GlobalF4 __restrict__ m4 = (GlobalF4)(uintptr_t)(T.m + head);
+    GlobalF4 __restrict__ v4 = (GlobalF4)(uintptr_t)(T.v + head);
+    GlobalConstU2 __restrict__ g2 = (GlobalConstU2)(uintptr_t)(T.g + head);
+    GlobalU2 __restrict__ lp2 = T.p_lp ? (GlobalU2)(uintptr_t)(T.p_lp + head) : nullptr;
+    // Everything the tile needs from the kernel arguments is made to exist here, in front of the
+    // prologue: otherwise the compiler sinks the argument loads of the five pointers below the
+    // prologue's early exit, and a wavefront pays a third dependent round trip to the scalar cache
+    // (arguments, norm result, arguments again) before its first load.
+    asm volatile("" : "+s"(p4), "+s"(m4), "+s"(v4), "+s"(g2), "+s"(lp2));
+
+    // The norm result is looked at only now, so that its scalar load (whose address is itself a kernel
+    // argument) is not in front of the work above.
+    float gscale;
+    if (!step_prologue(a.d_norm, a.c, gscale)) return;
+
     // Elements before the vector body (at most 63) and after it (at most 3), by the tensor's first tile.
     if (tile == 0) {
         const int64_t t = threadIdx.x;
@@ -278,12 +312,6 @@ void adamw_wide_kernel(const StepArgs a)
         const int64_t tail = T.numel - body_end;
         if (t >= 4 && t - 4 < tail) step_scalar_at<DT, L2>(T, body_end + (t - 4), gscale, a.c);
     }
-
-    f32x4_mem* __restrict__ p4 = reinterpret_cast<f32x4_mem*>(T.p + head);
-    f32x4_mem* __restrict__ m4 = reinterpret_cast<f32x4_mem*>(T.m + head);
-    f32x4_mem* __restrict__ v4 = reinterpret_cast<f32x4_mem*>(T.v + head);
-    const u32x2_mem* __restrict__ g2 = reinterpret_cast<const u32x2_mem*>(T.g + head);
-    u32x2_mem* __restrict__ lp2 = T.p_lp ? reinterpret_cast<u32x2_mem*>(T.p_lp + head) : nullptr;
 
     const int64_t q0 = ti * kStepTileQuads + threadIdx.x;
 
@@ -502,6 +530,7 @@ __global__ __launch_bounds__(kFinalThreads) void norm_finalize_kernel(const Norm
         r.norm = __builtin_sqrt(sum) / (double)loss_scale;
         r.found_inf = flag ? 1u : 0u;
         r.scale_bits = __float_as_uint(loss_scale);
+        r.inv_norm = 1.0 / (r.norm + 1e-6);
         *out = r;
     }
 }
@@ -514,6 +543,7 @@ __global__ void norm_refresh_kernel(zi_norm_result* r, float loss_scale)
         r->norm = __builtin_sqrt(r->sumsq) / (double)loss_scale;
         r->found_inf = r->found_inf ? 1u : 0u;
         r->scale_bits = __float_as_uint(loss_scale);
+        r->inv_norm = 1.0 / (r->norm + 1e-6);
     }
 }
 

@@ -13,7 +13,7 @@
 struct client_args {
     uint64_t p, m, v, g, p_lp;        /* device addresses */
     int64_t numel;
-    uint64_t d_norm, d_norm2;         /* device, 24 bytes each */
+    uint64_t d_norm, d_norm2;         /* device, sizeof(zi_norm_result) each */
     uint64_t d_workspace;
     uint64_t workspace_bytes;
     uint64_t hip_stream;

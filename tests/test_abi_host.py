@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(zi.zi_norm_result) == 24
+    assert ctypes.sizeof(zi.zi_norm_result) == 32
     assert ctypes.sizeof(zi.zi_tensor) == 48
     assert ctypes.sizeof(zi.zi_adamw_config) == 48
     assert ctypes.sizeof(zi.zi_chunk_segment) == 40
@@ -90,7 +90,7 @@ def test_step_rejects_bad_tensors():
 
 def test_norm_rejects_bad_arguments():
     g = np.zeros(64, np.uint16)
-    out = np.zeros(3, np.float64)
+    out = np.zeros(4, np.float64)
     ws = np.zeros(zi.zi_norm_workspace_bytes() // 8, np.float64)
     t = [(None, None, None, g, None)]
     nb = ws.nbytes

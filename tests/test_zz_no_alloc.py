@@ -124,8 +124,8 @@ def test_captured_into_a_graph_with_the_step():
     cfg = zi_cfg(w)
     eager, eager_tl = device_copy()
     graphed, graphed_tl = device_copy()
-    out_e = torch.zeros(3, dtype=torch.float64, device="cuda:0")
-    out_g = torch.zeros(3, dtype=torch.float64, device="cuda:0")
+    out_e = torch.zeros(4, dtype=torch.float64, device="cuda:0")
+    out_g = torch.zeros(4, dtype=torch.float64, device="cuda:0")
     zi.zi_grad_norm_noalloc(eager_tl, dt, 1.0, out_e)            # first call on this device: not under capture
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
