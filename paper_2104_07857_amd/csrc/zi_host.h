@@ -172,13 +172,17 @@ struct StepIssuer {
     {
         if (numel <= 0) return hipSuccess;
         zi::StepDesc d{};
-        d.p = p; d.m = m; d.v = v; d.g = g; d.p_lp = p_lp; d.numel = numel;
         const int h = choose_head(p, m, v, g, p_lp);
         d.head = (int32_t)(h < numel ? h : numel);
+        d.p_body = p + d.head; d.m_body = m + d.head; d.v_body = v + d.head; d.g_body = g + d.head;
+        d.lp_body = p_lp ? p_lp + d.head : nullptr;
+        d.numel = numel;
         const int64_t nquad = (numel - d.head) / zi::kQuad;
         int64_t nt = (nquad + zi::kStepTileQuads - 1) / zi::kStepTileQuads;
         if (nt < 1) nt = 1;                       // the first tile also owns the unaligned ends
         if (nt > 0x7FFFFFFF) return hipErrorInvalidValue;
+        d.nquad = nquad;
+        d.n_tiles = (uint32_t)nt;
         if (nt >= kSoloTiles) {                   // a launch of its own: no tensor lookup in the kernel
             zi::StepArgs solo{};
             solo.c = args.c;

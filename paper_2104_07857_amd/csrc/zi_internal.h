@@ -49,17 +49,23 @@ struct NormPartial {
 };
 
 // One tensor (or one segment of one) as the fused step sees it.  All pointers are device memory.
-// The first `head` elements are handled one by one; the 4-element lane vectors start after them
-// (the host picks `head` so that as much of the traffic as possible starts on a 128-byte line).
+// The first `head` elements are handled one by one; the 4-element lane vectors (the body) start
+// after them (the host picks `head` so that as much of the traffic as possible starts on a 128-byte
+// line).  Everything a workgroup would otherwise derive from numel and head is worked out once on
+// the host: a wavefront lives for a few microseconds, and every scalar instruction in front of its
+// first load is time with nothing in flight.
 struct StepDesc {
-    float* p;
-    float* m;
-    float* v;
-    const uint16_t* g;
-    uint16_t* p_lp;        // may be null
+    float* p_body;         // p + head
+    float* m_body;
+    float* v_body;
+    const uint16_t* g_body;
+    uint16_t* lp_body;     // p_lp + head, null if there is no copy
     int64_t numel;
+    int64_t nquad;         // whole quads of the body: (numel - head) / 4
     int32_t head;          // 0..63
     uint32_t first_tile;   // index of this tensor's first tile within the launch
+    uint32_t n_tiles;      // tiles of this tensor: max(1, ceil(nquad / kStepTileQuads))
+    uint32_t reserved;
 };
 
 struct StepArgs {

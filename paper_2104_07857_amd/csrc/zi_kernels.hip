@@ -136,16 +136,17 @@ __device__ __forceinline__ bool step_prologue(const zi_norm_result* d_norm, cons
     return true;
 }
 
+// One element of the unaligned ends, addressed relative to the body (i may be negative: the head).
 template <int DT, bool L2>
 __device__ __forceinline__ void step_scalar_at(const StepDesc& T, int64_t i, float gscale, const StepConsts& c)
 {
-    float p = T.p[i], m = T.m[i], v = T.v[i];
-    const float g = widen16<DT>(T.g[i]);
+    float p = T.p_body[i], m = T.m_body[i], v = T.v_body[i];
+    const float g = widen16<DT>(T.g_body[i]);
     adamw_element<L2>(p, m, v, g, gscale, c);
-    T.p[i] = p;
-    T.m[i] = m;
-    T.v[i] = v;
-    if (T.p_lp) T.p_lp[i] = (uint16_t)narrow16<DT>(p);
+    T.p_body[i] = p;
+    T.m_body[i] = m;
+    T.v_body[i] = v;
+    if (T.lp_body) T.lp_body[i] = (uint16_t)narrow16<DT>(p);
 }
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -267,33 +268,29 @@ void adamw_wide_kernel(const StepArgs a)
     }
     const StepDesc& T = a.t[d];
 
-    const int64_t head = T.head;
-    const int64_t nquad = (T.numel - head) / kQuad;        // whole quads of the aligned body
-    const int64_t body_end = head + nquad * kQuad;
+    const int64_t nquad = T.nquad;
 
     // XCD-aware renumbering.  Workgroup ids of the launch go round-robin to the XCDs, so the runs are
     // counted in launch-wide ids (a tensor that does not start on a run boundary keeps the XCD <->
     // contiguous-tiles correspondence); it is a bijection on every run of 8 * kStepXcdRun workgroups
     // that lies inside one tensor, and the workgroups of incomplete runs keep their tiles.
-    int64_t ti;
+    uint32_t tile;
     {
         constexpr uint32_t run = kXcds * kStepXcdRun;
-        int64_t ntiles = (nquad + kStepTileQuads - 1) / kStepTileQuads;
-        if (ntiles < 1) ntiles = 1;
         const uint32_t r = block % run;
         const uint32_t base = block - r;
         uint32_t nb = block;
-        if (base >= T.first_tile && (int64_t)(base - T.first_tile) + run <= ntiles)
+        if (base >= T.first_tile && T.n_tiles >= run && base - T.first_tile <= T.n_tiles - run)
             nb = base + (r % kXcds) * (uint32_t)kStepXcdRun + r / kXcds;
-        ti = (int64_t)(nb - T.first_tile);
+        tile = nb - T.first_tile;
     }
-    const int64_t tile = ti;
+    const int64_t ti = tile;
 
-    GlobalF4 __restrict__ p4 = (GlobalF4)(uintptr_t)(T.p + head);
-    GlobalF4 __restrict__ m4 = (GlobalF4)(uintptr_t)(T.m + head);
-    GlobalF4 __restrict__ v4 = (GlobalF4)(uintptr_t)(T.v + head);
-    GlobalConstU2 __restrict__ g2 = (GlobalConstU2)(uintptr_t)(T.g + head);
-    GlobalU2 __restrict__ lp2 = T.p_lp ? (GlobalU2)(uintptr_t)(T.p_lp + head) : nullptr;
+    GlobalF4 __restrict__ p4 = (GlobalF4)(uintptr_t)T.p_body;
+    GlobalF4 __restrict__ m4 = (GlobalF4)(uintptr_t)T.m_body;
+    GlobalF4 __restrict__ v4 = (GlobalF4)(uintptr_t)T.v_body;
+    GlobalConstU2 __restrict__ g2 = (GlobalConstU2)(uintptr_t)T.g_body;
+    GlobalU2 __restrict__ lp2 = (GlobalU2)(uintptr_t)T.lp_body;
     // Everything the tile needs from the kernel arguments is made to exist here, in front of the
     // prologue: otherwise the compiler sinks the argument loads of the five pointers below the
     // prologue's early exit, and a wavefront pays a third dependent round trip to the scalar cache
@@ -308,9 +305,11 @@ void adamw_wide_kernel(const StepArgs a)
     // Elements before the vector body (at most 63) and after it (at most 3), by the tensor's first tile.
     if (tile == 0) {
         const int64_t t = threadIdx.x;
-        if (t < head) step_scalar_at<DT, L2>(T, t, gscale, a.c);
-        const int64_t tail = T.numel - body_end;
-        if (t >= 4 && t - 4 < tail) step_scalar_at<DT, L2>(T, body_end + (t - 4), gscale, a.c);
+        const int64_t head = T.head;
+        if (t < head) step_scalar_at<DT, L2>(T, t - head, gscale, a.c);
+        const int64_t body = nquad * kQuad;
+        const int64_t tail = T.numel - head - body;
+        if (t >= 4 && t - 4 < tail) step_scalar_at<DT, L2>(T, body + (t - 4), gscale, a.c);
     }
 
     const int64_t q0 = ti * kStepTileQuads + threadIdx.x;
